@@ -1,0 +1,210 @@
+/*
+ * hat_mid.h -- C ABI of the cloud-side middle-submodel forward of HAT
+ * (arXiv 2503.18989) for AMD MI355X (gfx950).
+ *
+ * The problem (paper Sec. 2.4 "Our Proposed Framework", Sec. 3.1 "System
+ * Overview", Fig. 3): the cloud holds the decoder layers between the device's
+ * first m layers and the device's head, plus one KV cache per device (Sec. 2.1).
+ * At every inference step it receives hidden states from many devices -- prompt
+ * chunks of devices in the prefill phase (Sec. 2.1 batched inference, Sec. 3.3
+ * prompt chunking) and draft sequences to verify from devices in the decode
+ * phase (Sec. 3.4) -- processes them as one batch and returns the deep hidden
+ * states.  Devices join and leave between steps (Sec. 2.1 continuous batching).
+ *
+ * The layer is LLaMA-style: pre-RMSNorm, rotary embedding (rotate-half pairing:
+ * element i pairs with i + head_dim/2, angle pos * theta^(-2i/head_dim)),
+ * multi-head attention with as many KV heads as query heads, softmax scale
+ * 1/sqrt(head_dim), SwiGLU feed-forward, no biases, residual after each
+ * sub-block.  A row at absolute position p attends to keys 0..p of its own
+ * device only.
+ *
+ * Conventions
+ *  - "device pointer" = address in GPU memory (HBM) of the current HIP device;
+ *    "host pointer" = ordinary process memory.  Every struct is read during the
+ *    call only.
+ *  - The library allocates no GPU memory: KV pool and workspace are supplied by
+ *    the caller (sizes from hat_mid_kv_bytes / hat_mid_workspace_bytes, 256-byte
+ *    aligned) and stay owned by the caller, who must keep them alive until
+ *    hat_mid_destroy.  hat_mid_create copies the weights into the workspace in a
+ *    tiled layout; the caller's weight arrays may be freed once the stream work
+ *    of hat_mid_create has completed.
+ *  - All GPU work is enqueued on the HIP stream passed to the call
+ *    (a hipStream_t cast to void*; NULL = the default stream).  Calls return
+ *    once the work is enqueued; outputs are valid after the stream is synced.
+ *  - Consecutive calls on one handle must be stream-ordered (same stream, or
+ *    synchronised by the caller): they share the workspace.
+ *  - One caller thread per handle.  No exceptions cross the ABI: every call
+ *    returns a hat_status_t (or a size / pointer), and hat_mid_last_error gives
+ *    the text of the last failure on the handle.
+ *  - hat_mid_forward validates every segment and the page demand of the whole
+ *    step before it changes anything: on error no KV row, page or length moves.
+ */
+#ifndef HAT_MID_H
+#define HAT_MID_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hat_mid hat_mid_t; /* opaque handle */
+
+typedef enum {
+  HAT_OK = 0,
+  HAT_EINVAL = -1,  /* malformed argument (n <= 0, verify segment longer than 8, beyond max_pos ...) */
+  HAT_ENOMEM = -2,  /* KV pool exhausted for this step */
+  HAT_EPOS = -3,    /* start_pos beyond the device's cache length (would leave a gap) */
+  HAT_EDUP = -4,    /* the same device twice in one step */
+  HAT_EDEVICE = -5, /* device id outside [0, max_devices) */
+  HAT_EHIP = -6     /* a HIP runtime call failed */
+} hat_status_t;
+
+typedef enum { HAT_SEG_CHUNK = 0, HAT_SEG_VERIFY = 1 } hat_seg_kind_t;
+typedef enum { HAT_BF16 = 0, HAT_F32 = 1 } hat_dtype_t;
+
+#define HAT_PAGE_SIZE 16  /* tokens per KV page */
+#define HAT_MAX_VERIFY 8  /* longest verify segment */
+
+typedef struct {
+  int32_t n_layers;        /* decoder layers in the middle submodel */
+  int32_t d_model;         /* = n_heads * head_dim; multiple of 64 */
+  int32_t n_heads;
+  int32_t head_dim;        /* 64 or 128 */
+  int32_t d_ffn;           /* SwiGLU inner width (any positive value) */
+  float rms_eps;           /* added to the mean of squares, inside the root */
+  float rope_theta;
+  int32_t page_size;       /* must be HAT_PAGE_SIZE */
+  int32_t n_pages;         /* pool capacity; one page id addresses all layers */
+  int32_t max_devices;     /* device ids are 0 .. max_devices-1 */
+  int32_t max_step_tokens; /* upper bound on the rows of one step */
+  int32_t max_pos;         /* upper bound on any device's cache length */
+  int32_t io_dtype;        /* hat_dtype_t of hidden_in / hidden_out */
+} hat_mid_config_t;
+
+/* One layer's weights: device pointers to bf16 arrays, linear weights row-major
+ * [out_features, in_features], norm gains [d_model]. */
+typedef struct {
+  const void *attn_norm, *wq, *wk, *wv, *wo, *ffn_norm, *w_gate, *w_up, *w_down;
+} hat_mid_layer_weights_t;
+
+/* One device's rows in a step: n rows of hidden states at consecutive absolute
+ * positions start_pos .. start_pos+n-1.  kind does not change the mathematics
+ * (both are causal over prefix + own rows); it routes the attention work: a
+ * VERIFY segment (Sec. 3.4: the draft sequence verified in one step) has
+ * n <= HAT_MAX_VERIFY rows and takes the bandwidth-bound path, a CHUNK segment
+ * (Sec. 3.3) takes the matrix-core path.
+ * start_pos must satisfy 0 <= start_pos <= cache length of the device.
+ * start_pos < length first rolls the cache back to start_pos: that is how the
+ * rows of rejected draft tokens disappear (Sec. 3.4: the next round starts after
+ * the last accepted token).  A device not seen before starts with length 0. */
+typedef struct {
+  int32_t device_id;
+  int32_t kind;           /* hat_seg_kind_t */
+  int32_t n;
+  int32_t start_pos;
+  const void* hidden_in;  /* device pointer, [n, d_model] row-major, io_dtype */
+  void* hidden_out;       /* device pointer, [n, d_model] row-major, io_dtype; may equal hidden_in */
+} hat_mid_segment_t;
+
+/* Bytes of KV pool / workspace the configuration needs (0 if cfg is invalid). */
+size_t hat_mid_kv_bytes(const hat_mid_config_t* cfg);
+size_t hat_mid_workspace_bytes(const hat_mid_config_t* cfg);
+
+/* Builds a handle.  layers: host array of cfg->n_layers entries (device
+ * pointers inside).  kv_pool, workspace: device pointers, caller-owned.
+ * Enqueues the weight re-tiling on hip_stream.  *out is NULL on failure and the
+ * status says why (HAT_EINVAL for a bad config, HAT_EHIP for a runtime error). */
+hat_status_t hat_mid_create(const hat_mid_config_t* cfg, const hat_mid_layer_weights_t* layers,
+                            void* kv_pool, void* workspace, void* hip_stream, hat_mid_t** out);
+
+/* One inference step over a ragged batch (Sec. 3.1: hidden states of devices in
+ * different phases processed in one batch per step).  segs: host array.  For
+ * every segment the n output rows are written to hidden_out.  KV rows of the new
+ * tokens are appended to each device's cache; pages follow the fixed policy
+ * "lowest free id first; all rollback frees of the step, in array order, then
+ * allocations in array order".  Atomic on error. */
+hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream);
+
+/* The device left (Sec. 2.1: requests leave the batch): all its pages return to
+ * the pool, its length becomes 0.  Unknown-but-valid ids are a no-op. */
+hat_status_t hat_mid_release(hat_mid_t* h, int32_t device_id);
+
+/* Frees host-side state (pinned staging, events).  GPU buffers stay with the caller. */
+void hat_mid_destroy(hat_mid_t* h);
+
+/* Text of the last error on this handle ("" if none); valid until the next call. */
+const char* hat_mid_last_error(const hat_mid_t* h);
+
+/* ---- introspection and fixtures ------------------------------------------ */
+
+/* Cache length and page list of a device.  pages_out (host, may be NULL) receives
+ * at most cap ids; *n_pages_out (may be NULL) the number owned. */
+hat_status_t hat_mid_kv_query(const hat_mid_t* h, int32_t device_id, int32_t* kv_len, int32_t* pages_out,
+                              int32_t cap, int32_t* n_pages_out);
+
+/* Installs n cache rows of one layer at positions pos0..pos0+n-1 from device
+ * arrays k, v of shape [n, n_heads, head_dim] bf16 (k already rotated).  Rows
+ * must extend or overwrite the device's cache contiguously (pos0 <= length); the
+ * length becomes max(length, pos0+n) and missing pages are taken with the same
+ * lowest-free-id policy as forward.  Every layer has to be imported over the same
+ * range before the rows are attended to.  Synchronises the stream (fixture). */
+hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n,
+                               const void* k, const void* v, void* hip_stream);
+
+/* Mirror of import: copies rows pos0..pos0+n-1 of one layer out to k, v
+ * ([n, n_heads, head_dim] bf16 device arrays). */
+hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n,
+                               void* k, void* v, void* hip_stream);
+
+/* Rows and GPU time of the last completed step -- the pair the cloud's state
+ * monitor records every round (Sec. 3.2, Eq. 1-2).  Synchronises on the step's
+ * end event. */
+hat_status_t hat_mid_last_step_stats(hat_mid_t* h, int32_t* tokens, float* gpu_ms);
+
+/* ---- per-kernel timing (for roofline measurement) -------------------------- */
+
+typedef enum {
+  HAT_K_GATHER = 0,   /* hidden_in rows -> fp32 residual */
+  HAT_K_RMSNORM,      /* both norms */
+  HAT_K_GEMM_QKV,
+  HAT_K_ROPE_APPEND,
+  HAT_K_ATTN_CHUNK,
+  HAT_K_ATTN_VERIFY,
+  HAT_K_ATTN_MERGE,
+  HAT_K_GEMM_O,
+  HAT_K_GEMM_GATEUP,
+  HAT_K_GEMM_DOWN,
+  HAT_K_SCATTER,      /* residual -> hidden_out rows */
+  HAT_K_COUNT
+} hat_kernel_id_t;
+
+/* on != 0: later forwards bracket every kernel launch with HIP events on the
+ * launch stream.  Slows the step slightly; off by default. */
+hat_status_t hat_mid_set_profiling(hat_mid_t* h, int32_t on);
+
+/* Sums since the last call, per kernel id: GPU milliseconds and launch counts
+ * (host arrays of HAT_K_COUNT entries).  Synchronises the recorded events, then
+ * resets the sums. */
+hat_status_t hat_mid_kernel_times(hat_mid_t* h, float* ms, int32_t* launches);
+
+/* ---- stage dumps (for per-stage parity tests) ------------------------------ */
+
+typedef enum {
+  HAT_DUMP_XNORM = 0, /* attention-norm output, [T, d_model] */
+  HAT_DUMP_Q,         /* rotated queries, [T, d_model] */
+  HAT_DUMP_ATTN,      /* attention output before the O projection, [T, d_model] */
+  HAT_DUMP_XNORM2,    /* FFN-norm output (norm of the residual after the attention block), [T, d_model] */
+  HAT_DUMP_ACT        /* silu(gate)*up, [T, d_ffn] */
+} hat_dump_id_t;
+
+/* Copies one intermediate of the LAST layer of the last forward, rows in batch
+ * order, to dst (device pointer, row-major fp32).  Only meaningful right after a
+ * forward on the same stream. */
+hat_status_t hat_mid_debug_dump(hat_mid_t* h, int32_t which, void* dst, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HAT_MID_H */

@@ -1,0 +1,234 @@
+"""ctypes binding of include/hat_mid.h -- argument marshalling only.
+
+torch is used for device memory and streams (plumbing): tensors are allocated
+by the caller or here with torch.empty, and their data pointers are handed to
+the C ABI.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+CHUNK, VERIFY = 0, 1
+HAT_BF16, HAT_F32 = 0, 1
+STATUS = {0: "HAT_OK", -1: "HAT_EINVAL", -2: "HAT_ENOMEM", -3: "HAT_EPOS", -4: "HAT_EDUP", -5: "HAT_EDEVICE",
+          -6: "HAT_EHIP"}
+KERNEL_NAMES = ["gather", "rmsnorm", "gemm_qkv", "rope_append", "attn_chunk", "attn_verify", "attn_merge",
+                "gemm_o", "gemm_gateup", "gemm_down", "scatter"]
+DUMP_IDS = {"xnorm": 0, "q": 1, "attn": 2, "xnorm2": 3, "act": 4}
+EXPORTED_SYMBOLS = [
+    "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_release",
+    "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_import", "hat_mid_kv_export",
+    "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump",
+]
+
+
+class Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("d_ffn", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("page_size", C.c_int32),
+                ("n_pages", C.c_int32), ("max_devices", C.c_int32), ("max_step_tokens", C.c_int32),
+                ("max_pos", C.c_int32), ("io_dtype", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
+
+
+class CSegment(C.Structure):
+    _fields_ = [("device_id", C.c_int32), ("kind", C.c_int32), ("n", C.c_int32), ("start_pos", C.c_int32),
+                ("hidden_in", C.c_void_p), ("hidden_out", C.c_void_p)]
+
+
+class HatError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("%s: %s" % (STATUS.get(code, code), msg))
+        self.code = code
+
+
+def lib_path():
+    return os.path.join(HERE, "libhatmid.so")
+
+
+_LIB = None
+
+
+def load_library():
+    """Loads the built library; raises if it is missing (there is no fallback)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    p = lib_path()
+    if not os.path.exists(p):
+        raise ImportError("libhatmid.so is not built: run `python -m paper_2503_18989_amd.build` "
+                          "(hipcc, gfx950) first")
+    lib = C.CDLL(p)
+    vp, i32 = C.c_void_p, C.c_int32
+    lib.hat_mid_kv_bytes.restype = C.c_size_t
+    lib.hat_mid_kv_bytes.argtypes = [C.POINTER(Config)]
+    lib.hat_mid_workspace_bytes.restype = C.c_size_t
+    lib.hat_mid_workspace_bytes.argtypes = [C.POINTER(Config)]
+    lib.hat_mid_create.restype = i32
+    lib.hat_mid_create.argtypes = [C.POINTER(Config), C.POINTER(LayerWeights), vp, vp, vp, C.POINTER(vp)]
+    lib.hat_mid_forward.restype = i32
+    lib.hat_mid_forward.argtypes = [vp, C.POINTER(CSegment), i32, vp]
+    lib.hat_mid_release.restype = i32
+    lib.hat_mid_release.argtypes = [vp, i32]
+    lib.hat_mid_destroy.restype = None
+    lib.hat_mid_destroy.argtypes = [vp]
+    lib.hat_mid_last_error.restype = C.c_char_p
+    lib.hat_mid_last_error.argtypes = [vp]
+    lib.hat_mid_kv_query.restype = i32
+    lib.hat_mid_kv_query.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(i32)]
+    lib.hat_mid_kv_import.restype = i32
+    lib.hat_mid_kv_import.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
+    lib.hat_mid_kv_export.restype = i32
+    lib.hat_mid_kv_export.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
+    lib.hat_mid_last_step_stats.restype = i32
+    lib.hat_mid_last_step_stats.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
+    lib.hat_mid_set_profiling.restype = i32
+    lib.hat_mid_set_profiling.argtypes = [vp, i32]
+    lib.hat_mid_kernel_times.restype = i32
+    lib.hat_mid_kernel_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
+    lib.hat_mid_debug_dump.restype = i32
+    lib.hat_mid_debug_dump.argtypes = [vp, i32, vp, vp]
+    _LIB = lib
+    return lib
+
+
+@dataclass
+class Segment:
+    device_id: int
+    kind: int
+    start_pos: int
+    hidden_in: "object"          # torch tensor [n, d] on the GPU
+    hidden_out: "object" = None   # defaults to a fresh tensor
+
+
+class HatMid:
+    """hat_mid_create / hat_mid_forward / hat_mid_release and friends.
+
+    cfg: dict with n_layers, d_model, n_heads, head_dim, d_ffn, rms_eps,
+    rope_theta.  layers: list of dicts of bf16 CUDA tensors (names as in
+    hat_mid_layer_weights_t).
+    """
+
+    def __init__(self, cfg, layers, n_pages, max_devices=64, max_step_tokens=8192, max_pos=16384,
+                 io_dtype="bf16", stream=None):
+        import torch
+        self.torch = torch
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("paper_2503_18989_amd needs a GPU: there is no CPU path")
+        self.io_torch = torch.bfloat16 if io_dtype == "bf16" else torch.float32
+        self.cfg = Config(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"],
+                          cfg["rms_eps"], cfg["rope_theta"], 16, n_pages, max_devices, max_step_tokens, max_pos,
+                          HAT_BF16 if io_dtype == "bf16" else HAT_F32)
+        self.d = cfg["d_model"]
+        self.d_ffn = cfg["d_ffn"]
+        self.n_heads, self.head_dim = cfg["n_heads"], cfg["head_dim"]
+        kvb = self.lib.hat_mid_kv_bytes(C.byref(self.cfg))
+        wsb = self.lib.hat_mid_workspace_bytes(C.byref(self.cfg))
+        if kvb == 0 or wsb == 0:
+            raise HatError(-1, "invalid configuration")
+        self.kv_pool = torch.empty(kvb, dtype=torch.uint8, device="cuda")
+        self.workspace = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        arr = (LayerWeights * cfg["n_layers"])()
+        for l, w in enumerate(layers):
+            for name, _ in LayerWeights._fields_:
+                t = w[name]
+                assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous(), name
+                setattr(arr[l], name, t.data_ptr())
+        self._handle = C.c_void_p()
+        rc = self.lib.hat_mid_create(C.byref(self.cfg), arr, self.kv_pool.data_ptr(), self.workspace.data_ptr(),
+                                     self._stream(stream), C.byref(self._handle))
+        if rc != 0:
+            raise HatError(rc, "hat_mid_create failed")
+        torch.cuda.current_stream().synchronize() if stream is None else stream.synchronize()
+
+    def _stream(self, stream=None):
+        s = stream if stream is not None else self.torch.cuda.current_stream()
+        return C.c_void_p(s.cuda_stream)
+
+    def _check(self, rc):
+        if rc != 0:
+            raise HatError(rc, self.lib.hat_mid_last_error(self._handle).decode())
+
+    def forward(self, segments, stream=None):
+        """segments: list of Segment.  Returns the list of output tensors."""
+        torch = self.torch
+        n = len(segments)
+        arr = (CSegment * max(n, 1))()
+        outs = []
+        for i, s in enumerate(segments):
+            x = s.hidden_in
+            assert x.is_cuda and x.dtype == self.io_torch and x.is_contiguous() and x.shape[1] == self.d
+            out = s.hidden_out if s.hidden_out is not None else torch.empty_like(x)
+            outs.append(out)
+            arr[i] = CSegment(s.device_id, s.kind, x.shape[0], s.start_pos, x.data_ptr(), out.data_ptr())
+        self._check(self.lib.hat_mid_forward(self._handle, arr, n, self._stream(stream)))
+        return outs
+
+    def forward_raw(self, arr, n, stream_ptr):
+        """Pre-marshalled call for timing loops: arr = (CSegment * n)."""
+        rc = self.lib.hat_mid_forward(self._handle, arr, n, stream_ptr)
+        if rc != 0:
+            self._check(rc)
+
+    def release(self, device_id):
+        self._check(self.lib.hat_mid_release(self._handle, device_id))
+
+    def kv_query(self, device_id, cap=1 << 16):
+        ln, npg = C.c_int32(), C.c_int32()
+        buf = (C.c_int32 * cap)()
+        self._check(self.lib.hat_mid_kv_query(self._handle, device_id, C.byref(ln), buf, cap, C.byref(npg)))
+        return ln.value, list(buf[: npg.value])
+
+    def kv_import(self, device_id, layer, pos0, k, v, stream=None):
+        assert k.is_cuda and k.dtype == self.torch.bfloat16 and k.is_contiguous() and k.shape == v.shape
+        assert tuple(k.shape[1:]) == (self.n_heads, self.head_dim)
+        self._check(self.lib.hat_mid_kv_import(self._handle, device_id, layer, pos0, k.shape[0], k.data_ptr(),
+                                               v.data_ptr(), self._stream(stream)))
+
+    def kv_export(self, device_id, layer, pos0, n, stream=None):
+        torch = self.torch
+        k = torch.empty((n, self.n_heads, self.head_dim), dtype=torch.bfloat16, device="cuda")
+        v = torch.empty_like(k)
+        self._check(self.lib.hat_mid_kv_export(self._handle, device_id, layer, pos0, n, k.data_ptr(), v.data_ptr(),
+                                               self._stream(stream)))
+        return k, v
+
+    def last_step_stats(self):
+        tok, ms = C.c_int32(), C.c_float()
+        self._check(self.lib.hat_mid_last_step_stats(self._handle, C.byref(tok), C.byref(ms)))
+        return tok.value, ms.value
+
+    def set_profiling(self, on):
+        self._check(self.lib.hat_mid_set_profiling(self._handle, 1 if on else 0))
+
+    def kernel_times(self):
+        ms = (C.c_float * len(KERNEL_NAMES))()
+        cnt = (C.c_int32 * len(KERNEL_NAMES))()
+        self._check(self.lib.hat_mid_kernel_times(self._handle, ms, cnt))
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_NAMES)}
+
+    def debug_dump(self, which, T, stream=None):
+        torch = self.torch
+        cols = self.d_ffn if which == "act" else self.d
+        out = torch.empty((T, cols), dtype=torch.float32, device="cuda")
+        self._check(self.lib.hat_mid_debug_dump(self._handle, DUMP_IDS[which], out.data_ptr(), self._stream(stream)))
+        return out
+
+    def close(self):
+        if getattr(self, "_handle", None) is not None and self._handle.value:
+            self.lib.hat_mid_destroy(self._handle)
+            self._handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

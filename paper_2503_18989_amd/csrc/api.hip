@@ -1,0 +1,696 @@
+// Host side of the middle-submodel library: configuration, workspace carving,
+// the integer planner of a step (positions, page table, attention work lists)
+// and the launch sequence of the decoder layers.  Interface and semantics are
+// documented in include/hat_mid.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <set>
+#include <string>
+#include <vector>
+
+#include "../../include/hat_mid.h"
+#include "hat_kernels.h"
+#include "hat_layout.h"
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
+
+struct LayerDev {
+  bf16_t *wqkv, *wo, *wgu, *wd;
+  float *g_attn, *g_ffn;
+};
+
+struct Shapes {
+  int L, d, H, hd, F, Fpad;
+  int Nqkv, No, Ngu, Nd;  // padded weight rows
+  int Tcap;               // row capacity of activation buffers (multiple of 256)
+  int attn_target;        // workgroups an attention launch should reach
+  int chunk_items_cap, verify_items_cap, merge_cap;
+  int part_rows_cap;
+  size_t plan_words;
+};
+
+bool valid_cfg(const hat_mid_config_t* c) {
+  if (!c) return false;
+  if (c->n_layers <= 0 || c->n_heads <= 0 || c->d_ffn <= 0) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->d_model != c->n_heads * c->head_dim || c->d_model % 64 != 0) return false;
+  if (c->page_size != HAT_PAGE_SIZE || c->n_pages <= 0) return false;
+  if (c->max_devices <= 0 || c->max_step_tokens <= 0 || c->max_pos <= 0) return false;
+  if (c->io_dtype != HAT_BF16 && c->io_dtype != HAT_F32) return false;
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return false;
+  return true;
+}
+
+Shapes make_shapes(const hat_mid_config_t& c) {
+  Shapes s;
+  s.L = c.n_layers; s.d = c.d_model; s.H = c.n_heads; s.hd = c.head_dim; s.F = c.d_ffn;
+  s.Fpad = round_up(c.d_ffn, 64);
+  s.Nqkv = round_up(3 * s.d, 256);
+  s.No = round_up(s.d, 256);
+  s.Ngu = round_up(2 * s.Fpad, 256);
+  s.Nd = round_up(s.d, 256);
+  s.Tcap = round_up(c.max_step_tokens, 256);
+  s.attn_target = 1024;
+  if (const char* e = getenv("HAT_ATTN_TARGET")) s.attn_target = std::max(1, atoi(e));
+  const int per_head = (s.attn_target + s.H - 1) / s.H;
+  s.chunk_items_cap = 2 * per_head + s.Tcap / 128 + c.max_devices + 2;
+  s.verify_items_cap = 2 * per_head + c.max_devices + 2;
+  s.merge_cap = s.Tcap / 128 + 2 * c.max_devices + 2;
+  s.part_rows_cap = 128 * (2 * per_head + 2) + HAT_MAX_VERIFY * s.verify_items_cap;
+  s.plan_words = (size_t)3 * s.Tcap + 8 * (size_t)c.max_devices + 16 + (size_t)c.n_pages + c.max_devices +
+                 8 * ((size_t)s.chunk_items_cap + s.verify_items_cap) + 4 * (size_t)s.merge_cap + 64;
+  return s;
+}
+
+// carve the workspace; with base == nullptr only sizes are computed
+struct Carver {
+  unsigned char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base((unsigned char*)b) {}
+  template <class T>
+  T* take(size_t n) {
+    off = align_up(off, 256);
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+struct Buffers {
+  std::vector<LayerDev> layers;
+  double* inv_freq;
+  float* resid;
+  bf16_t *xn, *xn2, *qkv, *attn, *act;
+  float2* table;
+  float* part_o;
+  float2* part_ml;
+  int32_t* plan_dev;
+  int32_t* fixture_pages;
+};
+
+size_t carve(const hat_mid_config_t& c, const Shapes& s, void* base, Buffers* out) {
+  Carver cv(base);
+  Buffers b;
+  b.layers.resize(s.L);
+  for (int l = 0; l < s.L; ++l) {
+    b.layers[l].wqkv = cv.take<bf16_t>((size_t)s.Nqkv * s.d);
+    b.layers[l].wo = cv.take<bf16_t>((size_t)s.No * s.d);
+    b.layers[l].wgu = cv.take<bf16_t>((size_t)s.Ngu * s.d);
+    b.layers[l].wd = cv.take<bf16_t>((size_t)s.Nd * s.Fpad);
+    b.layers[l].g_attn = cv.take<float>(s.d);
+    b.layers[l].g_ffn = cv.take<float>(s.d);
+  }
+  b.inv_freq = cv.take<double>(s.hd / 2);
+  b.resid = cv.take<float>((size_t)s.Tcap * s.d);
+  b.xn = cv.take<bf16_t>((size_t)s.Tcap * s.d);
+  b.xn2 = cv.take<bf16_t>((size_t)s.Tcap * s.d);
+  b.qkv = cv.take<bf16_t>((size_t)s.Tcap * 3 * s.d);
+  b.attn = cv.take<bf16_t>((size_t)s.Tcap * s.d);
+  b.act = cv.take<bf16_t>((size_t)s.Tcap * s.Fpad);
+  b.table = cv.take<float2>((size_t)s.Tcap * (s.hd / 2));
+  b.part_o = cv.take<float>((size_t)s.part_rows_cap * s.d);
+  b.part_ml = cv.take<float2>((size_t)s.part_rows_cap * s.H);
+  b.plan_dev = cv.take<int32_t>(s.plan_words);
+  b.fixture_pages = cv.take<int32_t>((size_t)(c.max_pos + 15) / 16 + 2);
+  if (out) *out = b;
+  return align_up(cv.off, 256);
+}
+
+struct DeviceState {
+  int len = 0;
+  std::vector<int32_t> pages;
+};
+
+constexpr int kPlanBufs = 3;
+
+}  // namespace
+
+struct hat_mid {
+  hat_mid_config_t cfg;
+  Shapes s;
+  Buffers b;
+  bf16_t* pool;
+  size_t layer_pool_elems;
+
+  std::set<int32_t> free_pages;
+  std::vector<DeviceState> dev;
+
+  int32_t* plan_host[kPlanBufs] = {nullptr, nullptr, nullptr};
+  hipEvent_t plan_ev[kPlanBufs] = {nullptr, nullptr, nullptr};
+  bool plan_ev_used[kPlanBufs] = {false, false, false};
+  int plan_next = 0;
+
+  hipEvent_t ev_begin = nullptr, ev_end = nullptr;
+  bool have_step = false;
+  int last_tokens = 0;
+
+  bool profiling = false;
+  struct Rec { int id; hipEvent_t a, b; };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> ev_pool;
+
+  std::string err;
+};
+
+namespace {
+
+hat_status_t fail(hat_mid* h, hat_status_t st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (h) h->err = buf;
+  return st;
+}
+
+#define HIP_TRY(h, expr)                                                                          \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) return fail(h, HAT_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+int32_t take_lowest(hat_mid* h) {
+  auto it = h->free_pages.begin();
+  int32_t id = *it;
+  h->free_pages.erase(it);
+  return id;
+}
+
+hipEvent_t get_event(hat_mid* h) {
+  if (!h->ev_pool.empty()) {
+    hipEvent_t e = h->ev_pool.back();
+    h->ev_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// brackets one launch with events when profiling is on
+struct Timed {
+  hat_mid* h;
+  hipStream_t st;
+  int id;
+  hipEvent_t a = nullptr, b = nullptr;
+  Timed(hat_mid* h_, hipStream_t st_, int id_) : h(h_), st(st_), id(id_) {
+    if (h->profiling) {
+      a = get_event(h);
+      b = get_event(h);
+      if (a) (void)hipEventRecord(a, st);
+    }
+  }
+  ~Timed() {
+    if (h->profiling && a && b) {
+      (void)hipEventRecord(b, st);
+      h->recs.push_back({id, a, b});
+    }
+  }
+};
+
+#define LAUNCH(h, st, id, call)                                                                      \
+  do {                                                                                               \
+    hipError_t e_;                                                                                   \
+    {                                                                                                \
+      Timed t_(h, st, id);                                                                           \
+      e_ = (call);                                                                                   \
+    }                                                                                                \
+    if (e_ != hipSuccess) return fail(h, HAT_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));   \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t hat_mid_kv_bytes(const hat_mid_config_t* cfg) {
+  if (!valid_cfg(cfg)) return 0;
+  return (size_t)cfg->n_layers * cfg->n_pages * kv_page_elems(cfg->n_heads, cfg->head_dim) * sizeof(bf16_t);
+}
+
+size_t hat_mid_workspace_bytes(const hat_mid_config_t* cfg) {
+  if (!valid_cfg(cfg)) return 0;
+  Shapes s = make_shapes(*cfg);
+  return carve(*cfg, s, nullptr, nullptr);
+}
+
+hat_status_t hat_mid_create(const hat_mid_config_t* cfg, const hat_mid_layer_weights_t* layers, void* kv_pool,
+                            void* workspace, void* hip_stream, hat_mid_t** out) {
+  if (out) *out = nullptr;
+  if (!out || !valid_cfg(cfg) || !layers || !kv_pool || !workspace) return HAT_EINVAL;
+  if (((uintptr_t)kv_pool | (uintptr_t)workspace) & 255) return HAT_EINVAL;
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const hat_mid_layer_weights_t& w = layers[l];
+    if (!w.attn_norm || !w.wq || !w.wk || !w.wv || !w.wo || !w.ffn_norm || !w.w_gate || !w.w_up || !w.w_down)
+      return HAT_EINVAL;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  hat_mid* h = new hat_mid();
+  h->cfg = *cfg;
+  h->s = make_shapes(*cfg);
+  carve(*cfg, h->s, workspace, &h->b);
+  h->pool = (bf16_t*)kv_pool;
+  h->layer_pool_elems = (size_t)cfg->n_pages * kv_page_elems(cfg->n_heads, cfg->head_dim);
+  for (int i = 0; i < cfg->n_pages; ++i) h->free_pages.insert(i);
+  h->dev.resize(cfg->max_devices);
+
+  auto bail = [&](hipError_t e, const char* what) {
+    fprintf(stderr, "hat_mid_create: %s: %s\n", what, hipGetErrorString(e));
+    hat_mid_destroy(h);
+    return HAT_EHIP;
+  };
+  hipError_t e;
+  if ((e = hat_gemm_init()) != hipSuccess) return bail(e, "gemm init");
+  if ((e = hat_attn_init()) != hipSuccess) return bail(e, "attention init");
+  for (int i = 0; i < kPlanBufs; ++i) {
+    if ((e = hipHostMalloc((void**)&h->plan_host[i], h->s.plan_words * sizeof(int32_t), hipHostMallocDefault)) !=
+        hipSuccess)
+      return bail(e, "pinned plan buffer");
+    if ((e = hipEventCreateWithFlags(&h->plan_ev[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+  }
+  if ((e = hipEventCreate(&h->ev_begin)) != hipSuccess) return bail(e, "event");
+  if ((e = hipEventCreate(&h->ev_end)) != hipSuccess) return bail(e, "event");
+
+  // rotary frequencies theta^(-2i/hd), in double
+  {
+    std::vector<double> f(h->s.hd / 2);
+    for (int i = 0; i < h->s.hd / 2; ++i) f[i] = std::pow((double)cfg->rope_theta, -2.0 * i / h->s.hd);
+    if ((e = hipMemcpyAsync(h->b.inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice, st)) !=
+        hipSuccess)
+      return bail(e, "inv_freq upload");
+    if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "sync");
+  }
+  // weights -> P32 tiles
+  const Shapes& s = h->s;
+  for (int l = 0; l < s.L; ++l) {
+    const hat_mid_layer_weights_t& w = layers[l];
+    LayerDev& ld = h->b.layers[l];
+    if ((e = hat_launch_retile(ld.wqkv, s.Nqkv, s.d, (const bf16_t*)w.wq, (const bf16_t*)w.wk, (const bf16_t*)w.wv,
+                               s.d, s.d, 1, st)) != hipSuccess)
+      return bail(e, "retile qkv");
+    if ((e = hat_launch_retile(ld.wo, s.No, s.d, (const bf16_t*)w.wo, nullptr, nullptr, s.d, s.d, 0, st)) !=
+        hipSuccess)
+      return bail(e, "retile o");
+    if ((e = hat_launch_retile(ld.wgu, s.Ngu, s.d, (const bf16_t*)w.w_gate, (const bf16_t*)w.w_up, nullptr, s.F, s.d,
+                               2, st)) != hipSuccess)
+      return bail(e, "retile gate/up");
+    if ((e = hat_launch_retile(ld.wd, s.Nd, s.Fpad, (const bf16_t*)w.w_down, nullptr, nullptr, s.d, s.F, 0, st)) !=
+        hipSuccess)
+      return bail(e, "retile down");
+    if ((e = hat_launch_bf16_to_f32((const bf16_t*)w.attn_norm, ld.g_attn, s.d, st)) != hipSuccess)
+      return bail(e, "gain");
+    if ((e = hat_launch_bf16_to_f32((const bf16_t*)w.ffn_norm, ld.g_ffn, s.d, st)) != hipSuccess)
+      return bail(e, "gain");
+  }
+  *out = h;
+  return HAT_OK;
+}
+
+void hat_mid_destroy(hat_mid_t* h) {
+  if (!h) return;
+  (void)hipDeviceSynchronize();
+  for (int i = 0; i < kPlanBufs; ++i) {
+    if (h->plan_host[i]) (void)hipHostFree(h->plan_host[i]);
+    if (h->plan_ev[i]) (void)hipEventDestroy(h->plan_ev[i]);
+  }
+  if (h->ev_begin) (void)hipEventDestroy(h->ev_begin);
+  if (h->ev_end) (void)hipEventDestroy(h->ev_end);
+  for (auto& r : h->recs) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  for (auto e : h->ev_pool) (void)hipEventDestroy(e);
+  delete h;
+}
+
+const char* hat_mid_last_error(const hat_mid_t* h) { return h ? h->err.c_str() : "null handle"; }
+
+hat_status_t hat_mid_release(hat_mid_t* h, int32_t device_id) {
+  if (!h) return HAT_EINVAL;
+  if (device_id < 0 || device_id >= h->cfg.max_devices) return fail(h, HAT_EDEVICE, "device id %d out of range", device_id);
+  DeviceState& d = h->dev[device_id];
+  for (int32_t p : d.pages) h->free_pages.insert(p);
+  d.pages.clear();
+  d.len = 0;
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_kv_query(const hat_mid_t* h, int32_t device_id, int32_t* kv_len, int32_t* pages_out, int32_t cap,
+                              int32_t* n_pages_out) {
+  if (!h) return HAT_EINVAL;
+  if (device_id < 0 || device_id >= h->cfg.max_devices) return HAT_EDEVICE;
+  const DeviceState& d = h->dev[device_id];
+  if (kv_len) *kv_len = d.len;
+  if (n_pages_out) *n_pages_out = (int32_t)d.pages.size();
+  if (pages_out)
+    for (int i = 0; i < cap && i < (int)d.pages.size(); ++i) pages_out[i] = d.pages[i];
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
+  if (!h) return HAT_EINVAL;
+  if (!segs || n_segs <= 0) return fail(h, HAT_EINVAL, "no segments");
+  const hat_mid_config_t& c = h->cfg;
+  const Shapes& s = h->s;
+  hipStream_t st = (hipStream_t)hip_stream;
+
+  // ---- validate everything before touching state
+  if (n_segs > c.max_devices) return fail(h, HAT_EINVAL, "more segments (%d) than devices", n_segs);
+  std::vector<char> seen(c.max_devices, 0);
+  long total = 0;
+  for (int i = 0; i < n_segs; ++i) {
+    const hat_mid_segment_t& g = segs[i];
+    if (g.device_id < 0 || g.device_id >= c.max_devices)
+      return fail(h, HAT_EDEVICE, "segment %d: device id %d out of range", i, g.device_id);
+    if ((g.kind != HAT_SEG_CHUNK && g.kind != HAT_SEG_VERIFY) || g.n <= 0 || g.start_pos < 0)
+      return fail(h, HAT_EINVAL, "segment %d: bad kind/n/start", i);
+    if (g.kind == HAT_SEG_VERIFY && g.n > HAT_MAX_VERIFY)
+      return fail(h, HAT_EINVAL, "segment %d: verify segment of %d rows (max %d)", i, g.n, HAT_MAX_VERIFY);
+    if ((long)g.start_pos + g.n > c.max_pos) return fail(h, HAT_EINVAL, "segment %d: beyond max_pos", i);
+    if (!g.hidden_in || !g.hidden_out) return fail(h, HAT_EINVAL, "segment %d: null hidden pointer", i);
+    if (seen[g.device_id]) return fail(h, HAT_EDUP, "segment %d: device %d twice in one step", i, g.device_id);
+    seen[g.device_id] = 1;
+    if (g.start_pos > h->dev[g.device_id].len)
+      return fail(h, HAT_EPOS, "segment %d: start %d beyond cache length %d", i, g.start_pos, h->dev[g.device_id].len);
+    total += g.n;
+  }
+  if (total > c.max_step_tokens) return fail(h, HAT_EINVAL, "step of %ld rows exceeds max_step_tokens", total);
+  {
+    long free_after = (long)h->free_pages.size(), need = 0;
+    for (int i = 0; i < n_segs; ++i) {
+      const hat_mid_segment_t& g = segs[i];
+      const long have = (long)h->dev[g.device_id].pages.size();
+      const long keep = (g.start_pos + 15) / 16;
+      free_after += have - keep;
+      need += (g.start_pos + g.n + 15) / 16 - keep;
+    }
+    if (need > free_after) return fail(h, HAT_ENOMEM, "KV pool exhausted: need %ld pages, %ld free", need, free_after);
+  }
+
+  // ---- commit the page movements: all rollbacks, then all allocations
+  for (int i = 0; i < n_segs; ++i) {
+    DeviceState& d = h->dev[segs[i].device_id];
+    const size_t keep = (size_t)(segs[i].start_pos + 15) / 16;
+    while (d.pages.size() > keep) {
+      h->free_pages.insert(d.pages.back());
+      d.pages.pop_back();
+    }
+    d.len = segs[i].start_pos;
+  }
+  const int T = (int)total, S = n_segs;
+  int np_total = 0;
+  for (int i = 0; i < n_segs; ++i) {
+    DeviceState& d = h->dev[segs[i].device_id];
+    const size_t want = (size_t)(segs[i].start_pos + segs[i].n + 15) / 16;
+    while (d.pages.size() < want) d.pages.push_back(take_lowest(h));
+    d.len = segs[i].start_pos + segs[i].n;
+    np_total += (int)d.pages.size();
+  }
+
+  // ---- plan blob
+  const int bi = h->plan_next;
+  h->plan_next = (h->plan_next + 1) % kPlanBufs;
+  if (h->plan_ev_used[bi]) HIP_TRY(h, hipEventSynchronize(h->plan_ev[bi]));
+  int32_t* P = h->plan_host[bi];
+  size_t w = 0;
+  auto take = [&](size_t n, size_t align_words) {
+    w = align_up(w, align_words);
+    size_t o = w;
+    w += n;
+    return o;
+  };
+  const size_t o_pos = take(T, 1), o_dst = take(T, 1), o_tseg = take(T, 1);
+  const size_t o_toff = take(S + 1, 1), o_sstart = take(S, 1), o_spt = take(S, 1);
+  const size_t o_in = take(2 * (size_t)S, 2), o_out = take(2 * (size_t)S, 2);
+  const size_t o_pt = take(np_total, 1);
+
+  std::vector<HatAttnItem> citems, vitems;
+  std::vector<HatMergeItem> mitems;
+  {
+    int t = 0, pt = 0;
+    for (int i = 0; i < S; ++i) {
+      const hat_mid_segment_t& g = segs[i];
+      const DeviceState& d = h->dev[g.device_id];
+      P[o_toff + i] = t;
+      P[o_sstart + i] = g.start_pos;
+      P[o_spt + i] = pt;
+      uint64_t ip = (uint64_t)(uintptr_t)g.hidden_in, op = (uint64_t)(uintptr_t)g.hidden_out;
+      memcpy(&P[o_in + 2 * i], &ip, 8);
+      memcpy(&P[o_out + 2 * i], &op, 8);
+      for (size_t k = 0; k < d.pages.size(); ++k) P[o_pt + pt + k] = d.pages[k];
+      for (int r = 0; r < g.n; ++r) {
+        const int q = g.start_pos + r;
+        P[o_pos + t] = q;
+        P[o_dst + t] = d.pages[q >> 4] * 16 + (q & 15);
+        P[o_tseg + t] = i;
+        ++t;
+      }
+      pt += (int)d.pages.size();
+    }
+    P[o_toff + S] = T;
+  }
+
+  // ---- attention work lists
+  {
+    const int per_head = (s.attn_target + s.H - 1) / s.H;  // items wanted
+    int part_row = 0;
+    // verify segments: split each cache into key ranges of about equal size
+    long vkeys = 0;
+    int nver = 0;
+    for (int i = 0; i < S; ++i)
+      if (segs[i].kind == HAT_SEG_VERIFY) { vkeys += segs[i].start_pos + segs[i].n; ++nver; }
+    if (nver) {
+      long ch = (vkeys + per_head - 1) / per_head;
+      ch = std::max<long>(256, (ch + 127) / 128 * 128);
+      for (int i = 0; i < S; ++i) {
+        if (segs[i].kind != HAT_SEG_VERIFY) continue;
+        const int len = segs[i].start_pos + segs[i].n;
+        int ns = (int)((len + ch - 1) / ch);
+        ns = std::min(ns, 64);
+        if ((int)vitems.size() + ns > s.verify_items_cap - 1 || part_row + ns * segs[i].n > s.part_rows_cap) ns = 1;
+        const int step = round_up((len + ns - 1) / ns, 64);
+        ns = (len + step - 1) / step;
+        HatMergeItem m{P[o_toff + i], segs[i].n, part_row, ns};
+        for (int k = 0; k < ns; ++k) {
+          HatAttnItem it{};
+          it.seg = i; it.q0 = 0; it.nq = segs[i].n;
+          it.kv_begin = k * step; it.kv_end = std::min(len, (k + 1) * step);
+          it.part_row = ns > 1 ? part_row + k * segs[i].n : -1;
+          vitems.push_back(it);
+        }
+        if (ns > 1) {
+          mitems.push_back(m);
+          part_row += ns * segs[i].n;
+        }
+      }
+    }
+    // chunk segments: 128-row tiles, optionally split along the keys
+    int base_tiles = 0;
+    for (int i = 0; i < S; ++i)
+      if (segs[i].kind == HAT_SEG_CHUNK) base_tiles += (segs[i].n + 127) / 128;
+    if (base_tiles) {
+      const int want = (base_tiles * s.H >= s.attn_target) ? 1 : (s.attn_target + base_tiles * s.H - 1) / (base_tiles * s.H);
+      for (int i = 0; i < S; ++i) {
+        if (segs[i].kind != HAT_SEG_CHUNK) continue;
+        for (int q0 = 0; q0 < segs[i].n; q0 += 128) {
+          const int nq = std::min(128, segs[i].n - q0);
+          const int need = segs[i].start_pos + q0 + nq;
+          int ns = std::min(std::min(want, std::max(1, need / 256)), 16);
+          if ((int)citems.size() + ns > s.chunk_items_cap - 1 || part_row + ns * nq > s.part_rows_cap ||
+              (int)mitems.size() >= s.merge_cap - 1)
+            ns = 1;
+          const int step = round_up((need + ns - 1) / ns, 64);
+          ns = (need + step - 1) / step;
+          HatMergeItem m{P[o_toff + i] + q0, nq, part_row, ns};
+          for (int k = 0; k < ns; ++k) {
+            HatAttnItem it{};
+            it.seg = i; it.q0 = q0; it.nq = nq;
+            it.kv_begin = k * step; it.kv_end = std::min(need, (k + 1) * step);
+            it.part_row = ns > 1 ? part_row + k * nq : -1;
+            citems.push_back(it);
+          }
+          if (ns > 1) {
+            mitems.push_back(m);
+            part_row += ns * nq;
+          }
+        }
+      }
+    }
+    auto by_cost = [](const HatAttnItem& a, const HatAttnItem& b) {
+      return (long)(a.kv_end - a.kv_begin) * a.nq > (long)(b.kv_end - b.kv_begin) * b.nq;
+    };
+    std::stable_sort(citems.begin(), citems.end(), by_cost);
+    std::stable_sort(vitems.begin(), vitems.end(), by_cost);
+  }
+  const size_t o_ci = take(8 * citems.size(), 8), o_vi = take(8 * vitems.size(), 8), o_mi = take(4 * mitems.size(), 4);
+  if (w > s.plan_words) return fail(h, HAT_EINVAL, "internal: plan of %zu words exceeds capacity %zu", w, s.plan_words);
+  static_assert(sizeof(HatAttnItem) == 32 && sizeof(HatMergeItem) == 16, "plan item sizes");
+  if (!citems.empty()) memcpy(&P[o_ci], citems.data(), citems.size() * sizeof(HatAttnItem));
+  if (!vitems.empty()) memcpy(&P[o_vi], vitems.data(), vitems.size() * sizeof(HatAttnItem));
+  if (!mitems.empty()) memcpy(&P[o_mi], mitems.data(), mitems.size() * sizeof(HatMergeItem));
+
+  // ---- enqueue
+  HIP_TRY(h, hipEventRecord(h->ev_begin, st));
+  HIP_TRY(h, hipMemcpyAsync(h->b.plan_dev, P, w * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(h, hipEventRecord(h->plan_ev[bi], st));
+  h->plan_ev_used[bi] = true;
+
+  const int32_t* D = h->b.plan_dev;
+  HatPlanDev pd;
+  pd.T = T; pd.S = S;
+  pd.pos = D + o_pos; pd.kv_dst = D + o_dst; pd.tok_seg = D + o_tseg; pd.tok_off = D + o_toff;
+  pd.seg_start = D + o_sstart; pd.seg_pt = D + o_spt; pd.page_tbl = D + o_pt;
+  pd.in_ptr = (const uint64_t*)(D + o_in); pd.out_ptr = (const uint64_t*)(D + o_out);
+
+  LAUNCH(h, st, HAT_K_GATHER, hat_launch_gather(pd, h->b.resid, s.d, c.io_dtype, st));
+  LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_table(pd, h->b.inv_freq, h->b.table, s.hd / 2, st));
+
+  for (int l = 0; l < s.L; ++l) {
+    const LayerDev& ld = h->b.layers[l];
+    bf16_t* pool_l = h->pool + (size_t)l * h->layer_pool_elems;
+    LAUNCH(h, st, HAT_K_RMSNORM, hat_launch_rmsnorm(h->b.resid, ld.g_attn, h->b.xn, T, s.d, c.rms_eps, st));
+    HatGemm g{};
+    g.W = ld.wqkv; g.X = h->b.xn; g.K = s.d; g.T = T; g.Nw = s.Nqkv; g.Nout = 3 * s.d; g.outP = h->b.qkv;
+    g.epilogue = HAT_EPI_P32;
+    LAUNCH(h, st, HAT_K_GEMM_QKV, hat_launch_gemm(g, st));
+    LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_append(pd, h->b.qkv, h->b.table, pool_l, s.H, s.hd, st));
+    HatAttn a{};
+    a.qkv = h->b.qkv; a.pool_layer = pool_l; a.outP = h->b.attn; a.part_o = h->b.part_o; a.part_ml = h->b.part_ml;
+    a.H = s.H; a.hd = s.hd; a.d = s.d;
+    if (!citems.empty()) {
+      a.items = (const HatAttnItem*)(D + o_ci); a.n_items = (int)citems.size();
+      LAUNCH(h, st, HAT_K_ATTN_CHUNK, hat_launch_attn_chunk(pd, a, st));
+    }
+    if (!vitems.empty()) {
+      a.items = (const HatAttnItem*)(D + o_vi); a.n_items = (int)vitems.size();
+      LAUNCH(h, st, HAT_K_ATTN_VERIFY, hat_launch_attn_verify(pd, a, st));
+    }
+    if (!mitems.empty())
+      LAUNCH(h, st, HAT_K_ATTN_MERGE, hat_launch_attn_merge(a, (const HatMergeItem*)(D + o_mi), (int)mitems.size(), st));
+    g = HatGemm{};
+    g.W = ld.wo; g.X = h->b.attn; g.K = s.d; g.T = T; g.Nw = s.No; g.Nout = s.d; g.resid = h->b.resid;
+    g.epilogue = HAT_EPI_RESID;
+    LAUNCH(h, st, HAT_K_GEMM_O, hat_launch_gemm(g, st));
+    LAUNCH(h, st, HAT_K_RMSNORM, hat_launch_rmsnorm(h->b.resid, ld.g_ffn, h->b.xn2, T, s.d, c.rms_eps, st));
+    g = HatGemm{};
+    g.W = ld.wgu; g.X = h->b.xn2; g.K = s.d; g.T = T; g.Nw = s.Ngu; g.Nout = s.Fpad; g.outP = h->b.act;
+    g.epilogue = HAT_EPI_SWIGLU;
+    LAUNCH(h, st, HAT_K_GEMM_GATEUP, hat_launch_gemm(g, st));
+    g = HatGemm{};
+    g.W = ld.wd; g.X = h->b.act; g.K = s.Fpad; g.T = T; g.Nw = s.Nd; g.Nout = s.d; g.resid = h->b.resid;
+    g.epilogue = HAT_EPI_RESID;
+    LAUNCH(h, st, HAT_K_GEMM_DOWN, hat_launch_gemm(g, st));
+  }
+  LAUNCH(h, st, HAT_K_SCATTER, hat_launch_scatter(pd, h->b.resid, s.d, c.io_dtype, st));
+  HIP_TRY(h, hipEventRecord(h->ev_end, st));
+  h->have_step = true;
+  h->last_tokens = T;
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_last_step_stats(hat_mid_t* h, int32_t* tokens, float* gpu_ms) {
+  if (!h) return HAT_EINVAL;
+  if (!h->have_step) return fail(h, HAT_EINVAL, "no step has run yet");
+  HIP_TRY(h, hipEventSynchronize(h->ev_end));
+  float ms = 0.f;
+  HIP_TRY(h, hipEventElapsedTime(&ms, h->ev_begin, h->ev_end));
+  if (tokens) *tokens = h->last_tokens;
+  if (gpu_ms) *gpu_ms = ms;
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_set_profiling(hat_mid_t* h, int32_t on) {
+  if (!h) return HAT_EINVAL;
+  h->profiling = on != 0;
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_kernel_times(hat_mid_t* h, float* ms, int32_t* launches) {
+  if (!h || !ms || !launches) return HAT_EINVAL;
+  for (int i = 0; i < HAT_K_COUNT; ++i) { ms[i] = 0.f; launches[i] = 0; }
+  for (auto& r : h->recs) {
+    HIP_TRY(h, hipEventSynchronize(r.b));
+    float t = 0.f;
+    HIP_TRY(h, hipEventElapsedTime(&t, r.a, r.b));
+    ms[r.id] += t;
+    launches[r.id] += 1;
+    h->ev_pool.push_back(r.a);
+    h->ev_pool.push_back(r.b);
+  }
+  h->recs.clear();
+  return HAT_OK;
+}
+
+static hat_status_t fixture_pages(hat_mid_t* h, const DeviceState& d, int pos0, int n, hipStream_t st) {
+  const int p0 = pos0 >> 4, p1 = (pos0 + n - 1) >> 4;
+  HIP_TRY(h, hipStreamSynchronize(st));  // the staging area below is reused by every fixture call
+  HIP_TRY(h, hipMemcpy(h->b.fixture_pages, d.pages.data() + p0, (size_t)(p1 - p0 + 1) * sizeof(int32_t),
+                       hipMemcpyHostToDevice));
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n, const void* k,
+                               const void* v, void* hip_stream) {
+  if (!h) return HAT_EINVAL;
+  const hat_mid_config_t& c = h->cfg;
+  if (device_id < 0 || device_id >= c.max_devices) return fail(h, HAT_EDEVICE, "device id %d out of range", device_id);
+  if (layer < 0 || layer >= c.n_layers || n <= 0 || pos0 < 0 || !k || !v) return fail(h, HAT_EINVAL, "bad import arguments");
+  if ((long)pos0 + n > c.max_pos) return fail(h, HAT_EINVAL, "import beyond max_pos");
+  DeviceState& d = h->dev[device_id];
+  if (pos0 > d.len) return fail(h, HAT_EPOS, "import at %d beyond cache length %d", pos0, d.len);
+  const size_t want = (size_t)(pos0 + n + 15) / 16;
+  if (want > d.pages.size() && want - d.pages.size() > h->free_pages.size())
+    return fail(h, HAT_ENOMEM, "KV pool exhausted on import");
+  while (d.pages.size() < want) d.pages.push_back(take_lowest(h));
+  d.len = std::max(d.len, pos0 + n);
+  hipStream_t st = (hipStream_t)hip_stream;
+  hat_status_t rc = fixture_pages(h, d, pos0, n, st);
+  if (rc != HAT_OK) return rc;
+  HIP_TRY(h, hat_launch_kv_import(h->pool + (size_t)layer * h->layer_pool_elems, h->b.fixture_pages, pos0, n,
+                                  (const bf16_t*)k, (const bf16_t*)v, c.n_heads, c.head_dim, st));
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n, void* k,
+                               void* v, void* hip_stream) {
+  if (!h) return HAT_EINVAL;
+  const hat_mid_config_t& c = h->cfg;
+  if (device_id < 0 || device_id >= c.max_devices) return fail(h, HAT_EDEVICE, "device id %d out of range", device_id);
+  if (layer < 0 || layer >= c.n_layers || n <= 0 || pos0 < 0 || !k || !v) return fail(h, HAT_EINVAL, "bad export arguments");
+  const DeviceState& d = h->dev[device_id];
+  if (pos0 + n > d.len) return fail(h, HAT_EPOS, "export of rows %d..%d beyond cache length %d", pos0, pos0 + n, d.len);
+  hipStream_t st = (hipStream_t)hip_stream;
+  hat_status_t rc = fixture_pages(h, d, pos0, n, st);
+  if (rc != HAT_OK) return rc;
+  HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, h->b.fixture_pages, pos0, n,
+                                  (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, st));
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_debug_dump(hat_mid_t* h, int32_t which, void* dst, void* hip_stream) {
+  if (!h || !dst) return HAT_EINVAL;
+  if (!h->have_step) return fail(h, HAT_EINVAL, "no step has run yet");
+  const Shapes& s = h->s;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int T = h->last_tokens;
+  switch (which) {
+    case HAT_DUMP_XNORM: HIP_TRY(h, hat_launch_unpack_p32(h->b.xn, s.d, 0, s.d, T, (float*)dst, st)); break;
+    case HAT_DUMP_Q: HIP_TRY(h, hat_launch_unpack_p32(h->b.qkv, 3 * s.d, 0, s.d, T, (float*)dst, st)); break;
+    case HAT_DUMP_ATTN: HIP_TRY(h, hat_launch_unpack_p32(h->b.attn, s.d, 0, s.d, T, (float*)dst, st)); break;
+    case HAT_DUMP_XNORM2: HIP_TRY(h, hat_launch_unpack_p32(h->b.xn2, s.d, 0, s.d, T, (float*)dst, st)); break;
+    case HAT_DUMP_ACT: HIP_TRY(h, hat_launch_unpack_p32(h->b.act, s.Fpad, 0, s.F, T, (float*)dst, st)); break;
+    default: return fail(h, HAT_EINVAL, "unknown dump id %d", which);
+  }
+  return HAT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,412 @@
+// Prefix-causal attention over the paged KV cache, in two launch shapes:
+//
+//   chunk  -- a prompt chunk of a device in the prefill phase (paper Sec. 2.1
+//             chunked prefill, Sec. 3.3): many query rows, matrix-core bound.
+//             One workgroup = 128 query rows (4 waves x 32) of one head; K/V tiles
+//             of 64 keys are staged in LDS and shared by the four waves.
+//   verify -- the draft sequence of a device in the decode phase verified in one
+//             step (Sec. 3.4): at most 8 query rows against a long cache, HBM
+//             bound.  One workgroup = one (segment, head, key range); each wave
+//             streams every 4th pair of pages straight from global memory into
+//             MFMA operand registers (the page tiles are stored in operand order,
+//             so a wave instruction reads whole contiguous 512 B / 1 KB runs),
+//             then the four waves' partial results are merged through LDS.
+//
+// Both compute S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so a lane owns ONE query
+// column and 16 keys of it: the online softmax is lane-local except for one
+// exchange between the two lane halves, and the probabilities are already in the
+// B-operand order of O^T += V^T P^T (the V tile is stored in that key order).
+// Row at position p sees keys 0..p of its own device.  Long key ranges may be
+// split over several workgroups; those write (max, sum, unnormalised O) partials
+// that attn_merge combines.
+#include <hip/hip_runtime.h>
+
+#include "hat_kernels.h"
+#include "hat_layout.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct SegInfo {
+  int start, nseg, kv_len, tok0, npages;
+  const int32_t* pt;
+};
+
+__device__ __forceinline__ SegInfo seg_info(const HatPlanDev& p, int seg) {
+  SegInfo s;
+  s.start = p.seg_start[seg];
+  s.tok0 = p.tok_off[seg];
+  s.nseg = p.tok_off[seg + 1] - s.tok0;
+  s.kv_len = s.start + s.nseg;
+  s.npages = (s.kv_len + 15) >> 4;
+  s.pt = p.page_tbl + p.seg_pt[seg];
+  return s;
+}
+
+// Online-softmax update for one 32-key S^T tile held as 16 accumulator values.
+// key of value r: key0 + 8*(r/4) + 4*half + r%4.  Returns probabilities as the
+// two B operands (keys 0..15 / 16..31 of the tile) and rescales O.
+template <int NC>
+__device__ __forceinline__ void softmax_step(const f32x16& s_acc, float scale_log2, int key0, int half, int qpos,
+                                             float& m_run, float& l_run, f32x16 (&o)[NC], bf16x8& p0, bf16x8& p1) {
+  float sl[16];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int key = key0 + 8 * (r >> 2) + 4 * half + (r & 3);
+    sl[r] = (key <= qpos) ? s_acc[r] * scale_log2 : -INFINITY;
+    mx = fmaxf(mx, sl[r]);
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m_run, mx);
+  const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+  const float alpha = exp2f(m_run - m_safe);
+  float ps = 0.f;
+  float pv[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    pv[r] = exp2f(sl[r] - m_safe);
+    ps += pv[r];
+  }
+  l_run = l_run * alpha + ps;
+  m_run = m_new;
+#pragma unroll
+  for (int c = 0; c < NC; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[c][r] *= alpha;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    p0[j] = (__bf16)pv[j];
+    p1[j] = (__bf16)pv[8 + j];
+  }
+}
+
+// zero the V operand elements whose key lies at or beyond kv_len (stale memory
+// there may hold NaN patterns, and 0 * NaN would poison the accumulator)
+__device__ __forceinline__ bf16x8 clean_v(bf16x8 v, int page_key0, int half, int kv_len) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int key = page_key0 + 8 * (j >> 2) + 4 * half + (j & 3);
+    if (key >= kv_len) v[j] = (__bf16)0.f;
+  }
+  return v;
+}
+
+// ------------------------------------------------------------------ verify
+template <int HD>
+__global__ __launch_bounds__(256) void attn_verify_kernel(HatPlanDev p, HatAttn a) {
+  constexpr int NS = HD / 16;  // k-steps of Q K^T
+  constexpr int NC = HD / 32;  // 32-row blocks of O^T
+  constexpr int REC = 2 * 16 * HD;  // elements of one (page, head) record
+  __shared__ float lds_o[4][HAT_MAX_VERIFY_ROWS][HD];
+  __shared__ float lds_m[4][HAT_MAX_VERIFY_ROWS], lds_l[4][HAT_MAX_VERIFY_ROWS];
+
+  const HatAttnItem it = a.items[blockIdx.x];
+  const int head = blockIdx.y;
+  const SegInfo sg = seg_info(p, it.seg);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5, n = lane & 31;
+  const int qi = n < it.nq ? n : it.nq - 1;  // clamp idle columns onto a real row
+  const int qrow = sg.tok0 + it.q0 + qi;
+  const int qpos = sg.start + it.q0 + qi;
+  const float scale_log2 = kLog2e / sqrtf((float)HD);
+
+  bf16x8 qreg[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+    qreg[s] = *(const bf16x8*)(a.qkv + p32_index(qrow, head * HD + (2 * s + half) * 8, 3 * a.d));
+
+  f32x16 o[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[c][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  int kv_end = it.kv_end < sg.kv_len ? it.kv_end : sg.kv_len;
+  const int pair0 = it.kv_begin >> 5, pair1 = (kv_end + 31) >> 5;
+  const bf16_t* pool = a.pool_layer + (size_t)head * REC;
+  const size_t page_stride = (size_t)a.H * REC;
+
+  for (int pp = pair0 + wave; pp < pair1; pp += 4) {
+    const int key0 = pp << 5;
+    int ia = 2 * pp, ib = 2 * pp + 1;
+    ib = ib < sg.npages ? ib : sg.npages - 1;
+    const bf16_t* recA = pool + (size_t)sg.pt[ia] * page_stride;
+    const bf16_t* recB = pool + (size_t)sg.pt[ib] * page_stride;
+    const bf16_t* krec = (n < 16) ? recA : recB;
+    bf16x8 kreg[NS], va[NC], vb[NC];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) kreg[s] = *(const bf16x8*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      va[c] = *(const bf16x8*)(recA + 16 * HD + c * 512 + lane * 8);
+      vb[c] = *(const bf16x8*)(recB + 16 * HD + c * 512 + lane * 8);
+    }
+    f32x16 sacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[s], qreg[s], sacc, 0, 0, 0);
+    if (key0 + 32 > sg.kv_len) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        va[c] = clean_v(va[c], key0, half, sg.kv_len);
+        vb[c] = clean_v(vb[c], key0 + 16, half, sg.kv_len);
+      }
+    }
+    bf16x8 p0, p1;
+    softmax_step<NC>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[c], p0, o[c], 0, 0, 0);
+      o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[c], p1, o[c], 0, 0, 0);
+    }
+  }
+  l_run += __shfl_xor(l_run, 32);
+
+  // merge the four waves (each saw a disjoint quarter of the keys)
+  if (n < it.nq) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) lds_o[wave][n][32 * c + 8 * (r >> 2) + 4 * half + (r & 3)] = o[c][r];
+    if (half == 0) {
+      lds_m[wave][n] = m_run;
+      lds_l[wave][n] = l_run;
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < it.nq * (HD / 4); idx += 256) {
+    const int q = idx / (HD / 4), e = (idx % (HD / 4)) * 4;
+    float M = fmaxf(fmaxf(lds_m[0][q], lds_m[1][q]), fmaxf(lds_m[2][q], lds_m[3][q]));
+    const float Ms = (M == -INFINITY) ? 0.f : M;
+    float L = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = exp2f(lds_m[w][q] - Ms);
+      L += lds_l[w][q] * f;
+      const f32x4 v = *(const f32x4*)&lds_o[w][q][e];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) acc[x] += v[x] * f;
+    }
+    if (it.part_row < 0) {
+      const float inv = 1.0f / L;
+      bf16x4 ov;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) ov[x] = (__bf16)(acc[x] * inv);
+      *(bf16x4*)(a.outP + p32_index(sg.tok0 + it.q0 + q, head * HD + e, a.d)) = ov;
+    } else {
+      const size_t pr = (size_t)(it.part_row + q) * a.H + head;
+      *(f32x4*)(a.part_o + pr * HD + e) = acc;
+      if (e == 0) a.part_ml[pr] = make_float2(M, L);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ chunk
+template <int HD>
+__global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a) {
+  constexpr int NS = HD / 16;
+  constexpr int NC = HD / 32;
+  constexpr int REC = 2 * 16 * HD;        // elements of one (page, head) record
+  constexpr int RECB = REC * 2;           // bytes
+  constexpr int LPT = 4 * RECB / 16 / 256;  // 16-byte loads per thread per 64-key stage
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2][4 * RECB];
+
+  const HatAttnItem it = a.items[blockIdx.x];
+  const int head = blockIdx.y;
+  const SegInfo sg = seg_info(p, it.seg);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5, n = lane & 31;
+  const int wq0 = it.q0 + 32 * wave;  // first row of this wave, relative to the segment
+  int nq_w = it.nq - 32 * wave;       // valid rows of this wave
+  nq_w = nq_w > 32 ? 32 : nq_w;
+  const bool wave_live = nq_w > 0;
+  int qi = wq0 + (n < nq_w ? n : (nq_w > 0 ? nq_w - 1 : 0));
+  if (!wave_live) qi = it.q0;  // idle wave: any in-range row
+  const int qrow = sg.tok0 + qi;
+  const int qpos = sg.start + qi;
+  const int wave_last_pos = wave_live ? sg.start + wq0 + nq_w - 1 : -1;
+  const float scale_log2 = kLog2e / sqrtf((float)HD);
+
+  bf16x8 qreg[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+    qreg[s] = *(const bf16x8*)(a.qkv + p32_index(qrow, head * HD + (2 * s + half) * 8, 3 * a.d));
+
+  f32x16 o[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[c][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  // keys this item needs: [kv_begin, min(kv_end, last row's position + 1))
+  int kv_end = it.kv_end;
+  const int need = sg.start + it.q0 + it.nq;
+  kv_end = kv_end < need ? kv_end : need;
+  const int st0 = it.kv_begin >> 6, st1 = (kv_end + 63) >> 6;
+  const bf16_t* pool = a.pool_layer + (size_t)head * REC;
+  const size_t page_stride = (size_t)a.H * REC;
+
+  u32x4 regs[LPT];
+  auto gload = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int lin = i * 256 + threadIdx.x;        // 16-byte unit within the stage
+      const int pg = lin / (RECB / 16), off = lin % (RECB / 16);
+      int pi = st * 4 + pg;
+      pi = pi < sg.npages ? pi : sg.npages - 1;
+      regs[i] = *(const u32x4*)(pool + (size_t)sg.pt[pi] * page_stride + off * 8);
+    }
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * 256 + threadIdx.x) * 16]) = regs[i];
+  };
+
+  if (st0 < st1) {
+    gload(st0);
+    lstore(0);
+  }
+  __syncthreads();
+
+  for (int st = st0; st < st1; ++st) {
+    const int buf = (st - st0) & 1;
+    if (st + 1 < st1) gload(st + 1);
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      const int key0 = st * 64 + pr * 32;
+      if (key0 > wave_last_pos || key0 >= kv_end) continue;  // wave-uniform
+      const unsigned char* recA = &lds[buf][(2 * pr) * RECB];
+      const unsigned char* recB = recA + RECB;
+      const unsigned char* krec = (n < 16) ? recA : recB;
+      f32x16 sacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const bf16x8 kk = *(const bf16x8*)(krec + ((2 * s + half) * 16 + (n & 15)) * 16);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, qreg[s], sacc, 0, 0, 0);
+      }
+      bf16x8 p0, p1;
+      softmax_step<NC>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+      const bool tail = key0 + 32 > sg.kv_len;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        bf16x8 va = *(const bf16x8*)(recA + 16 * HD * 2 + c * 1024 + lane * 16);
+        bf16x8 vb = *(const bf16x8*)(recB + 16 * HD * 2 + c * 1024 + lane * 16);
+        if (tail) {
+          va = clean_v(va, key0, half, sg.kv_len);
+          vb = clean_v(vb, key0 + 16, half, sg.kv_len);
+        }
+        o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, p0, o[c], 0, 0, 0);
+        o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, p1, o[c], 0, 0, 0);
+      }
+    }
+    if (st + 1 < st1) lstore(buf ^ 1);
+    __syncthreads();
+  }
+  l_run += __shfl_xor(l_run, 32);
+
+  if (n < nq_w) {
+    const int row = wq0 + n;  // relative to segment
+    if (it.part_row < 0) {
+      const float inv = 1.0f / l_run;
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 ov;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(o[c][4 * g + e] * inv);
+          *(bf16x4*)(a.outP + p32_index(sg.tok0 + row, head * HD + 32 * c + 8 * g + 4 * half, a.d)) = ov;
+        }
+    } else {
+      const size_t prow = (size_t)(it.part_row + 32 * wave + n) * a.H + head;
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 ov;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ov[e] = o[c][4 * g + e];
+          *(f32x4*)(a.part_o + prow * HD + 32 * c + 8 * g + 4 * half) = ov;
+        }
+      if (half == 0) a.part_ml[prow] = make_float2(m_run, l_run);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ merge
+// one thread per (row, head, 8 output features)
+template <int HD>
+__global__ void attn_merge_kernel(HatAttn a, const HatMergeItem* __restrict__ items) {
+  const HatMergeItem it = items[blockIdx.x];
+  const int head = blockIdx.y;
+  for (int idx = threadIdx.x; idx < it.nrows * (HD / 8); idx += blockDim.x) {
+    const int r = idx / (HD / 8), e = (idx % (HD / 8)) * 8;
+    float M = -INFINITY;
+    for (int s = 0; s < it.nsplit; ++s)
+      M = fmaxf(M, a.part_ml[(size_t)(it.part_row + s * it.nrows + r) * a.H + head].x);
+    float L = 0.f;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int s = 0; s < it.nsplit; ++s) {
+      const size_t pr = (size_t)(it.part_row + s * it.nrows + r) * a.H + head;
+      const float2 ml = a.part_ml[pr];
+      const float f = exp2f(ml.x - M);
+      L += ml.y * f;
+      const f32x4 v0 = *(const f32x4*)(a.part_o + pr * HD + e), v1 = *(const f32x4*)(a.part_o + pr * HD + e + 4);
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        acc[x] += v0[x] * f;
+        acc[4 + x] += v1[x] * f;
+      }
+    }
+    const float inv = 1.0f / L;
+    bf16x8 ov;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) ov[x] = (__bf16)(acc[x] * inv);
+    *(bf16x8*)(a.outP + p32_index(it.row0 + r, head * HD + e, a.d)) = ov;
+  }
+}
+
+}  // namespace
+
+hipError_t hat_attn_init() { return hipSuccess; }
+
+hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStream_t st) {
+  if (a.n_items <= 0) return hipSuccess;
+  dim3 grid(a.n_items, a.H);
+  if (a.hd == 128) attn_chunk_kernel<128><<<grid, 256, 0, st>>>(p, a);
+  else if (a.hd == 64) attn_chunk_kernel<64><<<grid, 256, 0, st>>>(p, a);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t hat_launch_attn_verify(const HatPlanDev& p, const HatAttn& a, hipStream_t st) {
+  if (a.n_items <= 0) return hipSuccess;
+  dim3 grid(a.n_items, a.H);
+  if (a.hd == 128) attn_verify_kernel<128><<<grid, 256, 0, st>>>(p, a);
+  else if (a.hd == 64) attn_verify_kernel<64><<<grid, 256, 0, st>>>(p, a);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t hat_launch_attn_merge(const HatAttn& a, const HatMergeItem* items, int n_items, hipStream_t st) {
+  if (n_items <= 0) return hipSuccess;
+  dim3 grid(n_items, a.H);
+  if (a.hd == 128) attn_merge_kernel<128><<<grid, 256, 0, st>>>(a, items);
+  else if (a.hd == 64) attn_merge_kernel<64><<<grid, 256, 0, st>>>(a, items);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}

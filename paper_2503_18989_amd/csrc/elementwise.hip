@@ -1,0 +1,305 @@
+// Bandwidth-bound kernels of the decoder layer: RMSNorm, rotary embedding fused
+// with the KV-cache append, the ragged gather/scatter between the callers'
+// per-device hidden-state arrays and the batch, and the layout conversions used
+// at create time and by the fixtures.  (Layer structure: paper Sec. 2.1; KV
+// cache: Sec. 2.1; hidden states in / deep hidden states out: Sec. 3.1, Fig. 3.)
+#include <hip/hip_runtime.h>
+
+#include "hat_kernels.h"
+#include "hat_layout.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+// ---------------------------------------------------------------- gather/scatter
+// one workgroup per batch row; io_dtype 0 = bf16, 1 = f32
+__global__ void gather_kernel(HatPlanDev p, float* __restrict__ resid, int d, int io_dtype) {
+  const int t = blockIdx.x;
+  const int s = p.tok_seg[t];
+  const int row = t - p.tok_off[s];
+  float* dst = resid + (size_t)t * d;
+  if (io_dtype == 0) {
+    const bf16_t* src = (const bf16_t*)p.in_ptr[s] + (size_t)row * d;
+    for (int i = threadIdx.x * 8; i < d; i += blockDim.x * 8) {
+      bf16x8 v = *(const bf16x8*)(src + i);
+      f32x4 a, b;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { a[e] = (float)v[e]; b[e] = (float)v[4 + e]; }
+      *(f32x4*)(dst + i) = a;
+      *(f32x4*)(dst + i + 4) = b;
+    }
+  } else {
+    const float* src = (const float*)p.in_ptr[s] + (size_t)row * d;
+    for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) *(f32x4*)(dst + i) = *(const f32x4*)(src + i);
+  }
+}
+
+__global__ void scatter_kernel(HatPlanDev p, const float* __restrict__ resid, int d, int io_dtype) {
+  const int t = blockIdx.x;
+  const int s = p.tok_seg[t];
+  const int row = t - p.tok_off[s];
+  const float* src = resid + (size_t)t * d;
+  if (io_dtype == 0) {
+    bf16_t* dst = (bf16_t*)p.out_ptr[s] + (size_t)row * d;
+    for (int i = threadIdx.x * 8; i < d; i += blockDim.x * 8) {
+      f32x4 a = *(const f32x4*)(src + i), b = *(const f32x4*)(src + i + 4);
+      bf16x8 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] = (__bf16)a[e]; v[4 + e] = (__bf16)b[e]; }
+      *(bf16x8*)(dst + i) = v;
+    }
+  } else {
+    float* dst = (float*)p.out_ptr[s] + (size_t)row * d;
+    for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) *(f32x4*)(dst + i) = *(const f32x4*)(src + i);
+  }
+}
+
+// ---------------------------------------------------------------- rotary table
+// table[t][i] = (cos, sin)(pos[t] * inv_freq[i]), angle and functions in double:
+// positions reach several thousand radians, where float arguments lose digits.
+__global__ void rope_table_kernel(HatPlanDev p, const double* __restrict__ inv_freq, float2* __restrict__ table,
+                                  int half) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= p.T * half) return;
+  const int t = idx / half, i = idx % half;
+  const double ang = (double)p.pos[t] * inv_freq[i];
+  double s, c;
+  sincos(ang, &s, &c);
+  table[idx] = make_float2((float)c, (float)s);
+}
+
+// ---------------------------------------------------------------- RMSNorm
+// one workgroup (256 threads) per row: y = x * rsqrt(mean(x^2) + eps) * gain,
+// written as bf16 in P32 layout.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ resid, const float* __restrict__ gain,
+                                                       bf16_t* __restrict__ outP, int d, float eps) {
+  const int t = blockIdx.x;
+  const float* x = resid + (size_t)t * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x * 8; i < d; i += 256 * 8) {
+    f32x4 a = *(const f32x4*)(x + i), b = *(const f32x4*)(x + i + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) ss += a[e] * a[e] + b[e] * b[e];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  __shared__ float part[4];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  ss = part[0] + part[1] + part[2] + part[3];
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x * 8; i < d; i += 256 * 8) {
+    f32x4 a = *(const f32x4*)(x + i), b = *(const f32x4*)(x + i + 4);
+    f32x4 ga = *(const f32x4*)(gain + i), gb = *(const f32x4*)(gain + i + 4);
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] = (__bf16)(a[e] * r * ga[e]); v[4 + e] = (__bf16)(b[e] * r * gb[e]); }
+    *(bf16x8*)(outP + p32_index(t, i, d)) = v;
+  }
+}
+
+// ---------------------------------------------------------------- RoPE + KV append
+// One thread per (row, head, octet pair): octets o and o + hd/16 hold the two
+// halves of 8 rotation pairs.  q is rotated in place; rotated k and v go to the
+// row's (page, slot) of this layer's pool.
+__global__ void rope_append_kernel(HatPlanDev p, bf16_t* __restrict__ qkv, const float2* __restrict__ table,
+                                   bf16_t* __restrict__ pool, int H, int hd) {
+  const int half_oct = hd >> 4;                 // octets per half head
+  const int per_row = H * half_oct;
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= p.T * per_row) return;
+  const int t = idx / per_row, rem = idx % per_row;
+  const int hh = rem / half_oct, o = rem % half_oct;
+  const int d = H * hd, row_len = 3 * d;
+  const int c_lo = hh * hd + o * 8, c_hi = c_lo + (hd >> 1);
+  const float2* cs = table + (size_t)t * (hd >> 1) + o * 8;
+
+  bf16_t* q_lo = qkv + p32_index(t, c_lo, row_len);
+  bf16_t* q_hi = qkv + p32_index(t, c_hi, row_len);
+  const bf16x8 ql = *(bf16x8*)q_lo, qh = *(bf16x8*)q_hi;
+  const bf16x8 kl = *(const bf16x8*)(qkv + p32_index(t, d + c_lo, row_len));
+  const bf16x8 kh = *(const bf16x8*)(qkv + p32_index(t, d + c_hi, row_len));
+  const bf16x8 vl = *(const bf16x8*)(qkv + p32_index(t, 2 * d + c_lo, row_len));
+  const bf16x8 vh = *(const bf16x8*)(qkv + p32_index(t, 2 * d + c_hi, row_len));
+  bf16x8 rql, rqh, rkl, rkh;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float c = cs[e].x, s = cs[e].y;
+    const float a = (float)ql[e], b = (float)qh[e];
+    rql[e] = (__bf16)(a * c - b * s);
+    rqh[e] = (__bf16)(b * c + a * s);
+    const float ka = (float)kl[e], kb = (float)kh[e];
+    rkl[e] = (__bf16)(ka * c - kb * s);
+    rkh[e] = (__bf16)(kb * c + ka * s);
+  }
+  *(bf16x8*)q_lo = rql;
+  *(bf16x8*)q_hi = rqh;
+
+  const int dst = p.kv_dst[t];
+  const int page = dst >> 4, slot = dst & 15;
+  bf16_t* kt = pool + ((size_t)page * H + hh) * kv_head_elems(hd);
+  bf16_t* vt = kt + 16 * hd;
+  *(bf16x8*)(kt + ktile_index(slot, o * 8)) = rkl;
+  *(bf16x8*)(kt + ktile_index(slot, o * 8 + (hd >> 1))) = rkh;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    vt[vtile_index(slot, o * 8 + e)] = vl[e];
+    vt[vtile_index(slot, o * 8 + (hd >> 1) + e)] = vh[e];
+  }
+}
+
+// ---------------------------------------------------------------- weight re-tiling
+__global__ void retile_kernel(bf16_t* __restrict__ dst, int Nw, int Kd, const bf16_t* __restrict__ s0,
+                              const bf16_t* __restrict__ s1, const bf16_t* __restrict__ s2, int n0, int Ks, int mode) {
+  // one thread per destination octet
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = (size_t)Nw * (Kd >> 3);
+  if (idx >= total) return;
+  // destination order: [panel][octet][row%32]
+  const int r32 = (int)(idx & 31);
+  const size_t po = idx >> 5;
+  const int oct = (int)(po % (size_t)(Kd >> 3));
+  const int R = (int)(po / (size_t)(Kd >> 3)) * 32 + r32;
+  const bf16_t* src = nullptr;
+  int sr = -1;
+  if (mode == 0) {
+    if (R < n0) { src = s0; sr = R; }
+  } else if (mode == 1) {
+    if (R < 3 * n0) { src = R < n0 ? s0 : R < 2 * n0 ? s1 : s2; sr = R % n0; }
+  } else {
+    const int blk = R >> 6, w = R & 63;
+    const int f = blk * 32 + (w & 31);
+    if (f < n0) { src = (w < 32) ? s0 : s1; sr = f; }
+  }
+  bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.f;
+  if (src) {
+    const int k = oct * 8;
+    if (k + 8 <= Ks) {
+      if ((Ks & 7) == 0) {
+        v = *(const bf16x8*)(src + (size_t)sr * Ks + k);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = src[(size_t)sr * Ks + k + e];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (k + e < Ks) v[e] = src[(size_t)sr * Ks + k + e];
+    }
+  }
+  *(bf16x8*)(dst + idx * 8) = v;
+}
+
+__global__ void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = (float)src[i];
+}
+
+// ---------------------------------------------------------------- fixtures
+// one thread per (row, head, octet)
+__global__ void kv_import_kernel(bf16_t* __restrict__ pool, const int32_t* __restrict__ pages, int pos0, int n,
+                                 const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int H, int hd) {
+  const int octs = hd >> 3;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * H * octs) return;
+  const int o = (int)(idx % octs);
+  const int hh = (int)((idx / octs) % H);
+  const int r = (int)(idx / ((size_t)octs * H));
+  const int pos = pos0 + r;
+  const int page = pages[(pos >> 4) - (pos0 >> 4)], slot = pos & 15;
+  bf16_t* kt = pool + ((size_t)page * H + hh) * kv_head_elems(hd);
+  bf16_t* vt = kt + 16 * hd;
+  const size_t so = ((size_t)r * H + hh) * hd + o * 8;
+  *(bf16x8*)(kt + ktile_index(slot, o * 8)) = *(const bf16x8*)(k + so);
+  const bf16x8 vv = *(const bf16x8*)(v + so);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) vt[vtile_index(slot, o * 8 + e)] = vv[e];
+}
+
+__global__ void kv_export_kernel(const bf16_t* __restrict__ pool, const int32_t* __restrict__ pages, int pos0, int n,
+                                 bf16_t* __restrict__ k, bf16_t* __restrict__ v, int H, int hd) {
+  const int octs = hd >> 3;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * H * octs) return;
+  const int o = (int)(idx % octs);
+  const int hh = (int)((idx / octs) % H);
+  const int r = (int)(idx / ((size_t)octs * H));
+  const int pos = pos0 + r;
+  const int page = pages[(pos >> 4) - (pos0 >> 4)], slot = pos & 15;
+  const bf16_t* kt = pool + ((size_t)page * H + hh) * kv_head_elems(hd);
+  const bf16_t* vt = kt + 16 * hd;
+  const size_t so = ((size_t)r * H + hh) * hd + o * 8;
+  *(bf16x8*)(k + so) = *(const bf16x8*)(kt + ktile_index(slot, o * 8));
+  bf16x8 vv;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) vv[e] = vt[vtile_index(slot, o * 8 + e)];
+  *(bf16x8*)(v + so) = vv;
+}
+
+__global__ void unpack_p32_kernel(const bf16_t* __restrict__ srcP, int row_len, int col0, int ncols, int T,
+                                  float* __restrict__ dst) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)T * ncols) return;
+  const int t = (int)(idx / ncols), c = (int)(idx % ncols);
+  dst[idx] = (float)srcP[p32_index(t, col0 + c, row_len)];
+}
+
+inline unsigned blocks_for(size_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
+
+}  // namespace
+
+hipError_t hat_launch_gather(const HatPlanDev& p, float* resid, int d, int io_dtype, hipStream_t st) {
+  gather_kernel<<<p.T, 256, 0, st>>>(p, resid, d, io_dtype);
+  return hipGetLastError();
+}
+hipError_t hat_launch_scatter(const HatPlanDev& p, const float* resid, int d, int io_dtype, hipStream_t st) {
+  scatter_kernel<<<p.T, 256, 0, st>>>(p, resid, d, io_dtype);
+  return hipGetLastError();
+}
+hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, float2* table, int half,
+                                 hipStream_t st) {
+  rope_table_kernel<<<blocks_for((size_t)p.T * half, 256), 256, 0, st>>>(p, inv_freq, table, half);
+  return hipGetLastError();
+}
+hipError_t hat_launch_rmsnorm(const float* resid, const float* gain, bf16_t* outP, int T, int d, float eps,
+                              hipStream_t st) {
+  rmsnorm_kernel<<<T, 256, 0, st>>>(resid, gain, outP, d, eps);
+  return hipGetLastError();
+}
+hipError_t hat_launch_rope_append(const HatPlanDev& p, bf16_t* qkv, const float2* table, bf16_t* pool_layer, int H,
+                                  int hd, hipStream_t st) {
+  const size_t n = (size_t)p.T * H * (hd >> 4);
+  rope_append_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, H, hd);
+  return hipGetLastError();
+}
+hipError_t hat_launch_retile(bf16_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1, const bf16_t* src2,
+                             int n0, int Ks, int mode, hipStream_t st) {
+  const size_t n = (size_t)Nw * (Kd >> 3);
+  retile_kernel<<<blocks_for(n, 256), 256, 0, st>>>(dst, Nw, Kd, src0, src1, src2, n0, Ks, mode);
+  return hipGetLastError();
+}
+hipError_t hat_launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStream_t st) {
+  bf16_to_f32_kernel<<<blocks_for(n, 256), 256, 0, st>>>(src, dst, n);
+  return hipGetLastError();
+}
+hipError_t hat_launch_kv_import(bf16_t* pool_layer, const int32_t* pages, int pos0, int n, const bf16_t* k,
+                                const bf16_t* v, int H, int hd, hipStream_t st) {
+  const size_t cnt = (size_t)n * H * (hd >> 3);
+  kv_import_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, pages, pos0, n, k, v, H, hd);
+  return hipGetLastError();
+}
+hipError_t hat_launch_kv_export(const bf16_t* pool_layer, const int32_t* pages, int pos0, int n, bf16_t* k, bf16_t* v,
+                                int H, int hd, hipStream_t st) {
+  const size_t cnt = (size_t)n * H * (hd >> 3);
+  kv_export_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, pages, pos0, n, k, v, H, hd);
+  return hipGetLastError();
+}
+hipError_t hat_launch_unpack_p32(const bf16_t* srcP, int row_len, int col0, int ncols, int T, float* dst,
+                                 hipStream_t st) {
+  unpack_p32_kernel<<<blocks_for((size_t)T * ncols, 256), 256, 0, st>>>(srcP, row_len, col0, ncols, T, dst);
+  return hipGetLastError();
+}

@@ -1,0 +1,105 @@
+// Launch interface between the host side of the library and its HIP kernels.
+// All pointers are device pointers unless stated otherwise; every function
+// enqueues on `st` and returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+
+constexpr int HAT_MAX_VERIFY_ROWS = 8;  // query rows of a verify work item
+
+// ---- GEMM: out[t, f] = sum_k X[t, k] * W[f, k], operands in P32 layout ------
+enum HatEpilogue {
+  HAT_EPI_P32 = 0,     // bf16 result, P32 layout, row length Nout
+  HAT_EPI_SWIGLU = 1,  // W rows interleaved (32 gate, 32 up): silu(gate)*up, P32, row length Nout
+  HAT_EPI_RESID = 2    // resid[t, f] += result  (fp32 row-major, leading dim Nout)
+};
+
+struct HatGemm {
+  const bf16_t* W;  // P32 [Nw, K], Nw multiple of 256, padding rows zero
+  const bf16_t* X;  // P32 [>= roundup(T,32), K]
+  int K;            // multiple of 64
+  int T;            // valid rows of X
+  int Nw;           // rows of W including padding
+  int Nout;         // logical output features (EPI_SWIGLU: Nw/2 >= Nout)
+  bf16_t* outP;     // EPI_P32 / EPI_SWIGLU
+  float* resid;     // EPI_RESID
+  int epilogue;
+};
+hipError_t hat_launch_gemm(const HatGemm& g, hipStream_t st);
+hipError_t hat_gemm_init();  // one-time function attributes (dynamic LDS size)
+
+// ---- weight re-tiling (create time) -----------------------------------------
+// dst: P32 [Nw, Kd].  mode 0: row R <- src0[R] (R < n0), else 0.
+// mode 1 (qkv): rows [0,n0) <- src0, [n0,2n0) <- src1, [2n0,3n0) <- src2.
+// mode 2 (gate/up): row R: blk=R/64, w=R%64; f = 32*blk + w%32; (w<32 ? src0 : src1)[f], zero if f >= n0.
+// Source rows have Ks elements (Ks <= Kd; columns beyond Ks are zero).
+hipError_t hat_launch_retile(bf16_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1,
+                             const bf16_t* src2, int n0, int Ks, int mode, hipStream_t st);
+hipError_t hat_launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStream_t st);
+
+// ---- per-step plan as seen by the kernels -----------------------------------
+struct HatPlanDev {
+  int T, S;
+  const int32_t* pos;       // [T] absolute position of each row
+  const int32_t* kv_dst;    // [T] page*16 + slot where the row's K/V go
+  const int32_t* tok_seg;   // [T] segment of each row
+  const int32_t* tok_off;   // [S+1] first row of each segment
+  const int32_t* seg_start; // [S]
+  const int32_t* seg_pt;    // [S] offset of the segment's page list in page_tbl
+  const int32_t* page_tbl;
+  const uint64_t* in_ptr;   // [S] hidden_in
+  const uint64_t* out_ptr;  // [S] hidden_out
+};
+
+hipError_t hat_launch_gather(const HatPlanDev& p, float* resid, int d, int io_dtype, hipStream_t st);
+hipError_t hat_launch_scatter(const HatPlanDev& p, const float* resid, int d, int io_dtype, hipStream_t st);
+hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, float2* table, int half, hipStream_t st);
+hipError_t hat_launch_rmsnorm(const float* resid, const float* gain, bf16_t* outP, int T, int d, float eps,
+                              hipStream_t st);
+// qkv: P32 [., 3d]; rotates q in place, writes rotated k and v into the pool of one layer
+hipError_t hat_launch_rope_append(const HatPlanDev& p, bf16_t* qkv, const float2* table, bf16_t* pool_layer,
+                                  int H, int hd, hipStream_t st);
+
+// ---- attention ---------------------------------------------------------------
+// One work item = 32*QB query rows of one segment against keys [kv_begin, kv_end).
+struct HatAttnItem {
+  int32_t seg;       // segment index
+  int32_t q0;        // first query row, relative to the segment
+  int32_t nq;        // valid query rows in this item
+  int32_t kv_begin;  // multiple of 32
+  int32_t kv_end;    // exclusive; keys beyond the causal limit are masked
+  int32_t part_row;  // >= 0: first row of this item's partial result; -1: write the final output
+  int32_t pad0, pad1;
+};
+struct HatMergeItem {
+  int32_t row0;      // first batch row
+  int32_t nrows;
+  int32_t part_row;  // partial rows of split i start at part_row + i*nrows
+  int32_t nsplit;
+};
+struct HatAttn {
+  const bf16_t* qkv;         // P32 [., 3d]; q = columns [0, d)
+  const bf16_t* pool_layer;  // this layer's pages
+  bf16_t* outP;              // P32 [., d]
+  float* part_o;             // [part rows][H][hd] unnormalised partial outputs
+  float2* part_ml;           // [part rows][H] (running max in log2 units, sum)
+  const HatAttnItem* items;
+  int n_items;
+  int H, hd, d;
+};
+hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStream_t st);
+hipError_t hat_launch_attn_verify(const HatPlanDev& p, const HatAttn& a, hipStream_t st);
+hipError_t hat_launch_attn_merge(const HatAttn& a, const HatMergeItem* items, int n_items, hipStream_t st);
+hipError_t hat_attn_init();
+
+// ---- fixtures ------------------------------------------------------------------
+// k, v: [n, H, hd] bf16 plain; pages: device array of the page ids covering the rows
+hipError_t hat_launch_kv_import(bf16_t* pool_layer, const int32_t* pages, int pos0, int n, const bf16_t* k,
+                                const bf16_t* v, int H, int hd, hipStream_t st);
+hipError_t hat_launch_kv_export(const bf16_t* pool_layer, const int32_t* pages, int pos0, int n, bf16_t* k,
+                                bf16_t* v, int H, int hd, hipStream_t st);
+// P32 [., ncols_total] columns [col0, col0+ncols) -> fp32 row-major [T, ncols]
+hipError_t hat_launch_unpack_p32(const bf16_t* srcP, int row_len, int col0, int ncols, int T, float* dst,
+                                 hipStream_t st);
