@@ -1,0 +1,327 @@
+#!/usr/bin/env python3
+"""Benchmark of the middle-submodel forward on one MI355X.
+
+Metric: middle-submodel hidden tokens/s on the 7B-shaped single-device workload
+(30 decoder layers, d 4096, 32 heads x 128, FFN 11008, bf16; a 2048-row prompt fed
+as 8 chunks of 256 against the growing paged KV cache).  One "step" = one
+hat_mid_forward over one 256-row chunk (all kernels of the path, all 30 layers);
+steps cycle through the 8 chunk positions, releasing the device after the 8th.
+Inputs are resident in HBM before the timed region.
+
+Besides the contract line it reports, in the same JSON object:
+  roofline      the dominant kernel class of that workload (by GPU time), timed
+                with HIP events on the launch stream inside the library
+  kernels       every kernel class of the step: average duration and roofline
+  legs          chunk-attention MFMA fraction on a mixed-batch step and verify-
+                attention HBM GB/s on a verify-heavy step (30 devices)
+  cpu_baseline  the CPU oracle timed on this host on a bounded sample
+  paper_context end-to-end numbers the paper reports on other hardware
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import hat_inputs as hi  # noqa: E402
+
+PEAK_MFMA_BF16 = 2.5e15   # FLOP/s, dense
+PEAK_HBM = 8.0e12         # B/s
+SEED = 2000
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def gen_weights(cfg, seed, n_layers):
+    workers = min(16, os.cpu_count() or 8)
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        return list(ex.map(lambda l: hi.layer_weights(cfg, l, seed), range(n_layers)))
+
+
+def to_dev_bf16(x):
+    import torch
+    return torch.from_numpy(hi.bf16_bits(np.ascontiguousarray(x, np.float32)).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def upload(weights):
+    return [{k: to_dev_bf16(v) for k, v in w.items()} for w in weights]
+
+
+# ---------------------------------------------------------------- algorithmic work per kernel class
+def gemm_work(T, d, F):
+    """(flops, bytes) per launch of the four GEMM classes."""
+    w = {}
+    for name, N, K, out_b in (("gemm_qkv", 3 * d, d, 2), ("gemm_o", d, d, 8), ("gemm_gateup", 2 * F, d, 1),
+                              ("gemm_down", d, F, 8)):
+        flops = 2.0 * T * N * K
+        # weights once + activations in (bf16) + result out (bf16; fp32 read+write for the residual;
+        # gate/up writes T*F bf16 = half of its N columns)
+        byts = 2.0 * N * K + 2.0 * T * K + T * N * out_b
+        w[name] = (flops, byts)
+    return w
+
+
+def attn_work(segs, d):
+    """segs: list of (start, n).  Causal half not counted; K and V read once."""
+    flops = sum(4.0 * d * (n * s + n * (n + 1) / 2.0) for s, n in segs)
+    byts = sum(2.0 * (s + n) * d * 2 + 2.0 * n * d * 2 for s, n in segs)
+    return flops, byts
+
+
+def roof(flops, byts, sec):
+    """Binding roofline of one launch."""
+    t_m, t_h = flops / PEAK_MFMA_BF16, byts / PEAK_HBM
+    if t_m >= t_h:
+        a = flops / sec / 1e12
+        return {"bound": "mfma", "achieved": a, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
+                "frac": a / (PEAK_MFMA_BF16 / 1e12)}
+    a = byts / sec / 1e9
+    return {"bound": "hbm", "achieved": a, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": a / (PEAK_HBM / 1e9)}
+
+
+# ---------------------------------------------------------------- main workload
+def prepare_cfg2(m, cfg, n_chunks=8, chunk=256):
+    import torch
+    from paper_2503_18989_amd.binding import CSegment
+    xs, outs, arrs = [], [], []
+    for i in range(n_chunks):
+        x = to_dev_bf16(hi.hidden_rows(chunk, cfg["d_model"], SEED, i))
+        o = torch.empty_like(x)
+        arr = (CSegment * 1)()
+        arr[0] = CSegment(0, hi.CHUNK, chunk, i * chunk, x.data_ptr(), o.data_ptr())
+        xs.append(x); outs.append(o); arrs.append(arr)
+    return xs, outs, arrs
+
+
+def run_cfg2(m, arrs, steps, warmup):
+    import torch
+    stream = torch.cuda.current_stream()
+    sp = C.c_void_p(stream.cuda_stream)
+    n = len(arrs)
+
+    def one(i):
+        j = i % n
+        if j == 0:
+            m.release(0)
+        m.forward_raw(arrs[j], 1, sp)
+    for i in range(warmup):
+        one(i)
+    # continue the cycle where the warmup left it so that chunk positions stay consistent
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(warmup, warmup + steps):
+        one(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, e0.elapsed_time(e1) / 1e3
+
+
+def profile_classes(m, run_steps):
+    """Per kernel class: (avg seconds per launch, launches) with event bracketing on."""
+    import torch
+    m.set_profiling(True)
+    m.kernel_times()
+    run_steps()
+    torch.cuda.synchronize()
+    t = m.kernel_times()
+    m.set_profiling(False)
+    return {k: (ms / 1e3 / max(cnt, 1), cnt) for k, (ms, cnt) in t.items() if cnt}
+
+
+# ---------------------------------------------------------------- legs for the attention kernels
+def attention_legs(cfg7, dev_layers, n_layers=2):
+    """Chunk-attention MFMA fraction (mixed batch, config-3 shape) and verify-attention HBM GB/s
+    (config-4 shape: 30 devices, 5 draft rows each, cache lengths uniform in [1024, 8192])."""
+    import torch
+    from paper_2503_18989_amd import HatMid, Segment
+    cfg = hi.with_layers(cfg7, n_layers)
+    d, H, hd = cfg["d_model"], cfg["n_heads"], cfg["head_dim"]
+    out = {}
+    kbig = (torch.randn((8192, H, hd), device="cuda", dtype=torch.float32) * 1.28).to(torch.bfloat16)
+    vbig = (torch.randn((8192, H, hd), device="cuda", dtype=torch.float32) * 1.28).to(torch.bfloat16)
+
+    def install(m, lengths):
+        for dev, ln in enumerate(lengths):
+            for l in range(n_layers):
+                m.kv_import(dev, l, 0, kbig[:ln], vbig[:ln])
+
+    # --- verify-heavy step
+    lengths = hi.verify_lengths(SEED + 4)
+    pages = sum((ln + 5 * 8 + 15) // 16 for ln in lengths) + 64
+    m = HatMid(cfg, dev_layers[:n_layers], n_pages=pages, max_devices=32, max_step_tokens=256, max_pos=8192 + 64)
+    install(m, lengths)
+    xs = [to_dev_bf16(hi.hidden_rows(5, d, SEED + 4, dev)) for dev in range(30)]
+
+    def vstep():
+        segs = [Segment(dev, hi.VERIFY, lengths[dev], xs[dev]) for dev in range(30)]   # re-verify in place
+        m.forward(segs)
+    for _ in range(3):
+        vstep()
+    prof = profile_classes(m, lambda: [vstep() for _ in range(8)])
+    fl, by = attn_work([(ln, 5) for ln in lengths], d)
+    sec = prof["attn_verify"][0]
+    out["verify_attn"] = dict(roof(fl, by, sec), us_per_launch=sec * 1e6, algorithmic_bytes=by,
+                              workload="30 devices x 5 rows, cache lengths U[1024,8192], 7B-shaped layer")
+    out["verify_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
+    tok, ms = m.last_step_stats()
+    out["verify_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms}
+    m.close()
+    del m
+    torch.cuda.empty_cache()
+
+    # --- mixed step: 10 chunks + 20 verifies over prefixes U[256,4096]
+    pref = hi.mixed_prefixes(SEED + 3)
+    segs_desc = hi.mixed_step(SEED + 3, 0, pref)
+    pages = sum((p + n + 15) // 16 for (_, _, p, n) in segs_desc) + 64
+    T = sum(n for (_, _, _, n) in segs_desc)
+    m = HatMid(cfg, dev_layers[:n_layers], n_pages=pages, max_devices=32, max_step_tokens=max(T, 256), max_pos=8192)
+    install(m, pref)
+    xin = [to_dev_bf16(hi.hidden_rows(n, d, SEED + 3, dev)) for (dev, _, _, n) in segs_desc]
+
+    def mstep():
+        m.forward([Segment(dev, kind, p, x) for (dev, kind, p, n), x in zip(segs_desc, xin)])
+    for _ in range(3):
+        mstep()
+    prof = profile_classes(m, lambda: [mstep() for _ in range(8)])
+    chunks = [(p, n) for (_, kind, p, n) in segs_desc if kind == hi.CHUNK]
+    fl, by = attn_work(chunks, d)
+    sec = prof["attn_chunk"][0]
+    r = roof(fl, by, sec)
+    out["chunk_attn"] = dict(r, us_per_launch=sec * 1e6, mfma_frac=fl / sec / PEAK_MFMA_BF16,
+                             workload="10 chunks %s over prefixes U[256,4096] (+20 verify segments in the same step)"
+                             % sorted(n for _, n in chunks))
+    gw = gemm_work(T, d, cfg["d_ffn"])
+    out["mixed_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
+    out["mixed_step_gemm_mfma_frac"] = {k: gw[k][0] / prof[k][0] / PEAK_MFMA_BF16 for k in gw}
+    tok, ms = m.last_step_stats()
+    out["mixed_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms}
+    m.close()
+    return out
+
+
+# ---------------------------------------------------------------- CPU baseline (oracle)
+def cpu_baseline(cfg7, weights, n_layers=2, n_chunks=4, chunk=256):
+    from oracle import OracleMiddle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    cfg = hi.with_layers(cfg7, n_layers)
+    m = OracleMiddle(cfg, weights[:n_layers])
+    t0 = time.perf_counter()
+    for i in range(n_chunks):
+        m.forward([(0, i * chunk, hi.hidden_rows(chunk, cfg["d_model"], SEED, i))])
+    dt = time.perf_counter() - t0
+    scale = cfg7["n_layers"] / n_layers
+    return {"value": n_chunks * chunk / (dt * scale), "unit": "hidden tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d of 8 chunks (%d rows) through %d of %d layers in %.1f s, numpy float64; "
+                      "extrapolated linearly in layers" % (n_chunks, n_chunks * chunk, n_layers, cfg7["n_layers"], dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--no-legs", action="store_true", help="skip the attention legs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--layers", type=int, default=0, help="override depth (for profiling runs; the line is then not the metric)")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the middle-submodel forward on ONE GPU; --gpus %d is not supported "
+              "(no sharding, no collectives)" % a.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_18989_amd import HatMid
+    cfg = dict(hi.MID7B)
+    if a.layers:
+        cfg = hi.with_layers(cfg, a.layers)
+    L, d, F = cfg["n_layers"], cfg["d_model"], cfg["d_ffn"]
+    t0 = time.time()
+    weights = gen_weights(cfg, SEED, L)
+    log("weights generated in %.1f s" % (time.time() - t0))
+    dev_layers = upload(weights)
+    m = HatMid(cfg, dev_layers, n_pages=2048 // 16 + 8, max_devices=4, max_step_tokens=256, max_pos=2048)
+    xs, outs, arrs = prepare_cfg2(m, cfg)
+    wall, gpu_s = run_cfg2(m, arrs, a.steps, a.warmup)
+    sec = max(wall, gpu_s)
+    T = 256
+    value = T * a.steps / sec
+    log("cfg2: %.3f ms/step, %.0f hidden tokens/s" % (sec / a.steps * 1e3, value))
+
+    # per-class timing (separate pass, events around every launch)
+    def cyc():
+        sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        for i in range(16):
+            if i % 8 == 0:
+                m.release(0)
+            m.forward_raw(arrs[i % 8], 1, sp)
+    prof = profile_classes(m, cyc)
+    gw = gemm_work(T, d, F)
+    kernels = {}
+    for k, (s, cnt) in prof.items():
+        entry = {"us_per_launch": round(s * 1e6, 2), "launches_per_step": cnt / 16.0}
+        if k in gw:
+            entry.update(roof(gw[k][0], gw[k][1], s))
+            entry["mfma_frac"] = gw[k][0] / s / PEAK_MFMA_BF16
+        elif k == "attn_chunk":
+            # average over the 8 chunk positions
+            fl = np.mean([attn_work([(i * 256, 256)], d)[0] for i in range(8)])
+            by = np.mean([attn_work([(i * 256, 256)], d)[1] for i in range(8)])
+            entry.update(roof(fl, by, s))
+            entry["mfma_frac"] = fl / s / PEAK_MFMA_BF16
+        kernels[k] = entry
+    per_step = {k: v["us_per_launch"] * v["launches_per_step"] for k, v in kernels.items()}
+    dom = max((k for k in per_step if "bound" in kernels[k]), key=lambda k: per_step[k])
+    roofline = {k: kernels[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
+    roofline.update(kernel=dom, traffic=None, us_per_launch=kernels[dom]["us_per_launch"],
+                    algorithmic_bytes=gw[dom][1] if dom in gw else None,
+                    algorithmic_flops=gw[dom][0] if dom in gw else None)
+    # whole-step roofline: sum over classes of max(flop/peak, bytes/peak), matrix kernels only
+    ideal = L * sum(max(f / PEAK_MFMA_BF16, b / PEAK_HBM) for f, b in gw.values())
+    m.close()
+    del m
+    torch.cuda.empty_cache()
+
+    legs = None
+    if not a.no_legs:
+        legs = attention_legs(cfg, dev_layers)
+    cpu = None
+    if not a.no_cpu:
+        cpu = cpu_baseline(cfg, weights)
+
+    line = {
+        "metric": "middle-submodel hidden tokens/s; chunk-attn MFMA % peak; verify-attn HBM GB/s",
+        "value": value, "unit": "hidden tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": sec / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "7B-shaped middle submodel (%d layers, d 4096, 32x128 heads, FFN 11008), one device, "
+                               "2048-row prompt as 8 chunks of 256, bf16 KV in 16-token pages" % L,
+                   "rows_per_step": T, "io_dtype": "bf16"},
+        "gpu_event_ms_per_step": gpu_s / a.steps * 1e3, "host_wall_ms_per_step": wall / a.steps * 1e3,
+        "step_roofline_ms": ideal * 1e3, "step_roofline_frac": ideal / (sec / a.steps),
+        "roofline": roofline, "kernels": kernels, "legs": legs, "cpu_baseline": cpu,
+        "paper_context": "paper reports end-to-end TTFT -41..54% / TBT -41..77% on 30 Jetson devices + 8xA6000 "
+                         "(other hardware, whole system): context only, not a target",
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -204,6 +204,15 @@ typedef enum {
  * forward on the same stream. */
 hat_status_t hat_mid_debug_dump(hat_mid_t* h, int32_t which, void* dst, void* hip_stream);
 
+/* ---- tuning aid ------------------------------------------------------------------ */
+
+/* Forces the tile shape and K split of one GEMM class in later forwards
+ * (which: 0 = QKV, 1 = O, 2 = gate/up, 3 = down; tile: index into the library's
+ * tile table, -1 = automatic choice; ksplit: 1 = none, only honoured where the
+ * result is accumulated).  For sweeps of launch shapes; results do not change
+ * beyond fp32 summation order. */
+hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile, int32_t ksplit);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ DUMP_IDS = {"xnorm": 0, "q": 1, "attn": 2, "xnorm2": 3, "act": 4}
 EXPORTED_SYMBOLS = [
     "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_release",
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_import", "hat_mid_kv_export",
-    "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump",
+    "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
 ]
 
 
@@ -95,6 +95,8 @@ def load_library():
     lib.hat_mid_kernel_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     lib.hat_mid_debug_dump.restype = i32
     lib.hat_mid_debug_dump.argtypes = [vp, i32, vp, vp]
+    lib.hat_mid_debug_force_gemm.restype = i32
+    lib.hat_mid_debug_force_gemm.argtypes = [vp, i32, i32, i32]
     _LIB = lib
     return lib
 
@@ -221,6 +223,9 @@ class HatMid:
         out = torch.empty((T, cols), dtype=torch.float32, device="cuda")
         self._check(self.lib.hat_mid_debug_dump(self._handle, DUMP_IDS[which], out.data_ptr(), self._stream(stream)))
         return out
+
+    def force_gemm(self, which, tile, ksplit=1):
+        self._check(self.lib.hat_mid_debug_force_gemm(self._handle, which, tile, ksplit))
 
     def close(self):
         if getattr(self, "_handle", None) is not None and self._handle.value:

@@ -35,6 +35,7 @@ struct Shapes {
   int attn_target;        // workgroups an attention launch should reach
   int chunk_items_cap, verify_items_cap, merge_cap;
   int part_rows_cap;
+  int gemm_part_rows;     // rows of the split-K partial-sum buffer
   size_t plan_words;
 };
 
@@ -42,7 +43,7 @@ bool valid_cfg(const hat_mid_config_t* c) {
   if (!c) return false;
   if (c->n_layers <= 0 || c->n_heads <= 0 || c->d_ffn <= 0) return false;
   if (c->head_dim != 64 && c->head_dim != 128) return false;
-  if (c->d_model != c->n_heads * c->head_dim || c->d_model % 64 != 0) return false;
+  if (c->d_model != c->n_heads * c->head_dim || c->d_model % 64 != 0 || c->d_model > 8192) return false;
   if (c->page_size != HAT_PAGE_SIZE || c->n_pages <= 0) return false;
   if (c->max_devices <= 0 || c->max_step_tokens <= 0 || c->max_pos <= 0) return false;
   if (c->io_dtype != HAT_BF16 && c->io_dtype != HAT_F32) return false;
@@ -66,6 +67,7 @@ Shapes make_shapes(const hat_mid_config_t& c) {
   s.verify_items_cap = 2 * per_head + c.max_devices + 2;
   s.merge_cap = s.Tcap / 128 + 2 * c.max_devices + 2;
   s.part_rows_cap = 128 * (2 * per_head + 2) + HAT_MAX_VERIFY * s.verify_items_cap;
+  s.gemm_part_rows = 4096;
   s.plan_words = (size_t)3 * s.Tcap + 8 * (size_t)c.max_devices + 16 + (size_t)c.n_pages + c.max_devices +
                  8 * ((size_t)s.chunk_items_cap + s.verify_items_cap) + 4 * (size_t)s.merge_cap + 64;
   return s;
@@ -93,6 +95,7 @@ struct Buffers {
   float2* table;
   float* part_o;
   float2* part_ml;
+  float* gemm_part;
   int32_t* plan_dev;
   int32_t* fixture_pages;
 };
@@ -119,6 +122,7 @@ size_t carve(const hat_mid_config_t& c, const Shapes& s, void* base, Buffers* ou
   b.table = cv.take<float2>((size_t)s.Tcap * (s.hd / 2));
   b.part_o = cv.take<float>((size_t)s.part_rows_cap * s.d);
   b.part_ml = cv.take<float2>((size_t)s.part_rows_cap * s.H);
+  b.gemm_part = cv.take<float>((size_t)s.gemm_part_rows * s.d);
   b.plan_dev = cv.take<int32_t>(s.plan_words);
   b.fixture_pages = cv.take<int32_t>((size_t)(c.max_pos + 15) / 16 + 2);
   if (out) *out = b;
@@ -157,6 +161,9 @@ struct hat_mid {
   struct Rec { int id; hipEvent_t a, b; };
   std::vector<Rec> recs;
   std::vector<hipEvent_t> ev_pool;
+
+  int force_tile[4] = {-1, -1, -1, -1};   // tuning overrides per GEMM class (qkv, o, gate/up, down)
+  int force_ksplit[4] = {0, 0, 0, 0};
 
   std::string err;
 };
@@ -554,14 +561,27 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
   LAUNCH(h, st, HAT_K_GATHER, hat_launch_gather(pd, h->b.resid, s.d, c.io_dtype, st));
   LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_table(pd, h->b.inv_freq, h->b.table, s.hd / 2, st));
 
+  int nparts = 0;  // split-K partial sums of the previous residual GEMM still to be folded in
+  auto run_gemm = [&](int id, HatGemm& g, int* ksplit_out) -> hat_status_t {
+    const int cls = id == HAT_K_GEMM_QKV ? 0 : id == HAT_K_GEMM_O ? 1 : id == HAT_K_GEMM_GATEUP ? 2 : 3;
+    g.force_tile = h->force_tile[cls];
+    g.force_ksplit = h->force_ksplit[cls];
+    const HatGemmPlan gp = hat_gemm_plan(g);
+    if (ksplit_out) *ksplit_out = gp.ksplit;
+    LAUNCH(h, st, id, hat_launch_gemm(g, gp, st));
+    return HAT_OK;
+  };
   for (int l = 0; l < s.L; ++l) {
     const LayerDev& ld = h->b.layers[l];
     bf16_t* pool_l = h->pool + (size_t)l * h->layer_pool_elems;
-    LAUNCH(h, st, HAT_K_RMSNORM, hat_launch_rmsnorm(h->b.resid, ld.g_attn, h->b.xn, T, s.d, c.rms_eps, st));
+    LAUNCH(h, st, HAT_K_RMSNORM,
+           hat_launch_rmsnorm(h->b.resid, h->b.gemm_part, nparts, ld.g_attn, h->b.xn, T, s.d, c.rms_eps, st));
+    nparts = 0;
     HatGemm g{};
     g.W = ld.wqkv; g.X = h->b.xn; g.K = s.d; g.T = T; g.Nw = s.Nqkv; g.Nout = 3 * s.d; g.outP = h->b.qkv;
     g.epilogue = HAT_EPI_P32;
-    LAUNCH(h, st, HAT_K_GEMM_QKV, hat_launch_gemm(g, st));
+    hat_status_t rc = run_gemm(HAT_K_GEMM_QKV, g, nullptr);
+    if (rc != HAT_OK) return rc;
     LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_append(pd, h->b.qkv, h->b.table, pool_l, s.H, s.hd, st));
     HatAttn a{};
     a.qkv = h->b.qkv; a.pool_layer = pool_l; a.outP = h->b.attn; a.part_o = h->b.part_o; a.part_ml = h->b.part_ml;
@@ -578,19 +598,26 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
       LAUNCH(h, st, HAT_K_ATTN_MERGE, hat_launch_attn_merge(a, (const HatMergeItem*)(D + o_mi), (int)mitems.size(), st));
     g = HatGemm{};
     g.W = ld.wo; g.X = h->b.attn; g.K = s.d; g.T = T; g.Nw = s.No; g.Nout = s.d; g.resid = h->b.resid;
+    g.part = h->b.gemm_part; g.part_rows = s.gemm_part_rows;
     g.epilogue = HAT_EPI_RESID;
-    LAUNCH(h, st, HAT_K_GEMM_O, hat_launch_gemm(g, st));
-    LAUNCH(h, st, HAT_K_RMSNORM, hat_launch_rmsnorm(h->b.resid, ld.g_ffn, h->b.xn2, T, s.d, c.rms_eps, st));
+    int ks = 1;
+    if ((rc = run_gemm(HAT_K_GEMM_O, g, &ks)) != HAT_OK) return rc;
+    nparts = ks > 1 ? ks : 0;
+    LAUNCH(h, st, HAT_K_RMSNORM,
+           hat_launch_rmsnorm(h->b.resid, h->b.gemm_part, nparts, ld.g_ffn, h->b.xn2, T, s.d, c.rms_eps, st));
+    nparts = 0;
     g = HatGemm{};
     g.W = ld.wgu; g.X = h->b.xn2; g.K = s.d; g.T = T; g.Nw = s.Ngu; g.Nout = s.Fpad; g.outP = h->b.act;
     g.epilogue = HAT_EPI_SWIGLU;
-    LAUNCH(h, st, HAT_K_GEMM_GATEUP, hat_launch_gemm(g, st));
+    if ((rc = run_gemm(HAT_K_GEMM_GATEUP, g, nullptr)) != HAT_OK) return rc;
     g = HatGemm{};
     g.W = ld.wd; g.X = h->b.act; g.K = s.Fpad; g.T = T; g.Nw = s.Nd; g.Nout = s.d; g.resid = h->b.resid;
+    g.part = h->b.gemm_part; g.part_rows = s.gemm_part_rows;
     g.epilogue = HAT_EPI_RESID;
-    LAUNCH(h, st, HAT_K_GEMM_DOWN, hat_launch_gemm(g, st));
+    if ((rc = run_gemm(HAT_K_GEMM_DOWN, g, &ks)) != HAT_OK) return rc;
+    nparts = ks > 1 ? ks : 0;
   }
-  LAUNCH(h, st, HAT_K_SCATTER, hat_launch_scatter(pd, h->b.resid, s.d, c.io_dtype, st));
+  LAUNCH(h, st, HAT_K_SCATTER, hat_launch_scatter(pd, h->b.resid, h->b.gemm_part, nparts, s.d, c.io_dtype, st));
   HIP_TRY(h, hipEventRecord(h->ev_end, st));
   h->have_step = true;
   h->last_tokens = T;
@@ -673,6 +700,13 @@ hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, i
   if (rc != HAT_OK) return rc;
   HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, h->b.fixture_pages, pos0, n,
                                   (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, st));
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile, int32_t ksplit) {
+  if (!h || which < 0 || which > 3) return HAT_EINVAL;
+  h->force_tile[which] = tile;
+  h->force_ksplit[which] = ksplit;
   return HAT_OK;
 }
 

@@ -10,6 +10,7 @@
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -36,23 +37,30 @@ __global__ void gather_kernel(HatPlanDev p, float* __restrict__ resid, int d, in
   }
 }
 
-__global__ void scatter_kernel(HatPlanDev p, const float* __restrict__ resid, int d, int io_dtype) {
+__global__ void scatter_kernel(HatPlanDev p, const float* __restrict__ resid, const float* __restrict__ part,
+                               int nparts, int d, int io_dtype) {
   const int t = blockIdx.x;
   const int s = p.tok_seg[t];
   const int row = t - p.tok_off[s];
   const float* src = resid + (size_t)t * d;
-  if (io_dtype == 0) {
-    bf16_t* dst = (bf16_t*)p.out_ptr[s] + (size_t)row * d;
-    for (int i = threadIdx.x * 8; i < d; i += blockDim.x * 8) {
-      f32x4 a = *(const f32x4*)(src + i), b = *(const f32x4*)(src + i + 4);
-      bf16x8 v;
+  const size_t pstride = (size_t)p.T * d;
+  for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) {
+    f32x4 a = *(const f32x4*)(src + i);
+    for (int q = 0; q < nparts; ++q) {
+      const f32x4 b = *(const f32x4*)(part + q * pstride + (size_t)t * d + i);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { v[e] = (__bf16)a[e]; v[4 + e] = (__bf16)b[e]; }
-      *(bf16x8*)(dst + i) = v;
+      for (int e = 0; e < 4; ++e) a[e] += b[e];
     }
-  } else {
-    float* dst = (float*)p.out_ptr[s] + (size_t)row * d;
-    for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) *(f32x4*)(dst + i) = *(const f32x4*)(src + i);
+    if (io_dtype == 0) {
+      bf16_t* dst = (bf16_t*)p.out_ptr[s] + (size_t)row * d;
+      bf16x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (__bf16)a[e];
+      *(bf16x4*)(dst + i) = v;
+    } else {
+      float* dst = (float*)p.out_ptr[s] + (size_t)row * d;
+      *(f32x4*)(dst + i) = a;
+    }
   }
 }
 
@@ -71,32 +79,52 @@ __global__ void rope_table_kernel(HatPlanDev p, const double* __restrict__ inv_f
 }
 
 // ---------------------------------------------------------------- RMSNorm
-// one workgroup (256 threads) per row: y = x * rsqrt(mean(x^2) + eps) * gain,
-// written as bf16 in P32 layout.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ resid, const float* __restrict__ gain,
+// one workgroup (256 threads) per row: x = resid + pending split-K partial sums
+// (written back), y = x * rsqrt(mean(x^2) + eps) * gain as bf16 in P32 layout.
+// A row (<= 8192 floats) stays in registers between the two passes.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ resid, const float* __restrict__ part,
+                                                       int nparts, int T, const float* __restrict__ gain,
                                                        bf16_t* __restrict__ outP, int d, float eps) {
   const int t = blockIdx.x;
-  const float* x = resid + (size_t)t * d;
+  float* x = resid + (size_t)t * d;
+  const size_t pstride = (size_t)T * d;
+  constexpr int MAXV = 4;  // 256 threads * 8 floats * 4 = 8192 columns held in registers
+  f32x4 va[MAXV], vb[MAXV];
   float ss = 0.f;
-  for (int i = threadIdx.x * 8; i < d; i += 256 * 8) {
-    f32x4 a = *(const f32x4*)(x + i), b = *(const f32x4*)(x + i + 4);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) ss += a[e] * a[e] + b[e] * b[e];
+  for (int v = 0; v < MAXV; ++v) {
+    const int i = (v * 256 + threadIdx.x) * 8;
+    if (i < d) {
+      f32x4 a = *(const f32x4*)(x + i), b = *(const f32x4*)(x + i + 4);
+      for (int q = 0; q < nparts; ++q) {
+        const float* pp = part + q * pstride + (size_t)t * d + i;
+        const f32x4 pa = *(const f32x4*)pp, pb = *(const f32x4*)(pp + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { a[e] += pa[e]; b[e] += pb[e]; }
+      }
+      if (nparts > 0) { *(f32x4*)(x + i) = a; *(f32x4*)(x + i + 4) = b; }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ss += a[e] * a[e] + b[e] * b[e];
+      va[v] = a; vb[v] = b;
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-  __shared__ float part[4];
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __shared__ float red[4];
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
-  ss = part[0] + part[1] + part[2] + part[3];
+  ss = red[0] + red[1] + red[2] + red[3];
   const float r = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x * 8; i < d; i += 256 * 8) {
-    f32x4 a = *(const f32x4*)(x + i), b = *(const f32x4*)(x + i + 4);
-    f32x4 ga = *(const f32x4*)(gain + i), gb = *(const f32x4*)(gain + i + 4);
-    bf16x8 v;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { v[e] = (__bf16)(a[e] * r * ga[e]); v[4 + e] = (__bf16)(b[e] * r * gb[e]); }
-    *(bf16x8*)(outP + p32_index(t, i, d)) = v;
+  for (int v = 0; v < MAXV; ++v) {
+    const int i = (v * 256 + threadIdx.x) * 8;
+    if (i < d) {
+      const f32x4 ga = *(const f32x4*)(gain + i), gb = *(const f32x4*)(gain + i + 4);
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { o[e] = (__bf16)(va[v][e] * r * ga[e]); o[4 + e] = (__bf16)(vb[v][e] * r * gb[e]); }
+      *(bf16x8*)(outP + p32_index(t, i, d)) = o;
+    }
   }
 }
 
@@ -256,8 +284,9 @@ hipError_t hat_launch_gather(const HatPlanDev& p, float* resid, int d, int io_dt
   gather_kernel<<<p.T, 256, 0, st>>>(p, resid, d, io_dtype);
   return hipGetLastError();
 }
-hipError_t hat_launch_scatter(const HatPlanDev& p, const float* resid, int d, int io_dtype, hipStream_t st) {
-  scatter_kernel<<<p.T, 256, 0, st>>>(p, resid, d, io_dtype);
+hipError_t hat_launch_scatter(const HatPlanDev& p, const float* resid, const float* part, int nparts, int d,
+                              int io_dtype, hipStream_t st) {
+  scatter_kernel<<<p.T, 256, 0, st>>>(p, resid, part, nparts, d, io_dtype);
   return hipGetLastError();
 }
 hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, float2* table, int half,
@@ -265,9 +294,10 @@ hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, fl
   rope_table_kernel<<<blocks_for((size_t)p.T * half, 256), 256, 0, st>>>(p, inv_freq, table, half);
   return hipGetLastError();
 }
-hipError_t hat_launch_rmsnorm(const float* resid, const float* gain, bf16_t* outP, int T, int d, float eps,
-                              hipStream_t st) {
-  rmsnorm_kernel<<<T, 256, 0, st>>>(resid, gain, outP, d, eps);
+hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, bf16_t* outP, int T,
+                              int d, float eps, hipStream_t st) {
+  if (d > 8192) return hipErrorInvalidValue;
+  rmsnorm_kernel<<<T, 256, 0, st>>>(resid, part, nparts, T, gain, outP, d, eps);
   return hipGetLastError();
 }
 hipError_t hat_launch_rope_append(const HatPlanDev& p, bf16_t* qkv, const float2* table, bf16_t* pool_layer, int H,

@@ -10,12 +10,22 @@
 // one token and runs of 4 consecutive features, which is exactly an 8-byte piece
 // of the P32 layout of the *next* operand, so every epilogue stores coalesced.
 //
-// Tile: BF features x BT tokens per workgroup, BK = 64 per stage, waves arranged
-// WF x WT.  Global -> LDS goes through registers with the next stage's loads in
-// flight during the MFMAs of the current one (two LDS stages, one barrier per
-// stage).  LDS holds each 32-row panel's k-slab contiguously, so an MFMA operand
-// is one ds_read_b128 at lane*16 + immediate.
+// Data movement: global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4),
+// no register staging, into a ring of NSTAGE stages, so NSTAGE-1 k-tiles are in
+// flight while one is multiplied -- the weight stream of a small-batch step comes
+// from HBM and needs about a microsecond of loads in flight per CU.  Because the
+// P32 panel slab of a k-tile is contiguous in memory and is kept contiguous in
+// LDS, each wave instruction moves one 1 KB run, and an MFMA operand is one
+// ds_read_b128 at lane*16 + immediate, conflict-free without a swizzle.
+// LDS reads are issued from inline asm so that the compiler does not serialise
+// them behind the outstanding direct-to-LDS loads; the waits are explicit:
+// vmcnt for "my loads of this k-tile have landed", a barrier for "everyone's
+// have", lgkmcnt for the operand reads.
 #include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <type_traits>
+#include <utility>
 
 #include "hat_kernels.h"
 #include "hat_layout.h"
@@ -24,31 +34,71 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int BK = 64;
-constexpr int SLAB = (BK / 8) * 512;  // bytes of one panel's k-slab (32 rows x BK)
-constexpr int CPS = SLAB / 1024;      // 1 KB wave-chunks per slab
-
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
-template <int BF, int BT, int WF, int WT, int EPI>
-__global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit) {
-  constexpr int NW = WF * WT;
-  constexpr int MI = BF / WF / 32;  // feature blocks per wave
-  constexpr int NJ = BT / WT / 32;  // token blocks per wave
-  constexpr int PF = BF / 32, PT = BT / 32;
-  constexpr int NCH = (PF + PT) * CPS;  // 1 KB chunks per stage
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read(uint32_t addr) {
+  static_assert(OFF >= 0 && OFF < 65536, "ds_read offset field is 16 bits");
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// "operands have arrived": the wait is tied to the first register, the others are
+// threaded through empty asm statements (volatile asm keeps its order) so that no
+// MFMA using them can be scheduled above the wait.
+template <int N>
+__device__ __forceinline__ void wait_operands(bf16x8 (&v)[N]) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]));
+#pragma unroll
+  for (int i = 1; i < N; ++i) asm volatile("" : "+v"(v[i]));
+}
+
+template <int BF, int BT, int WF, int WT, int BKT, int NSTAGE>
+struct Tile {
+  static constexpr int NW = WF * WT;
+  static constexpr int MI = BF / WF / 32;   // feature blocks per wave
+  static constexpr int NJ = BT / WT / 32;   // token blocks per wave
+  static constexpr int PF = BF / 32, PT = BT / 32;
+  static constexpr int SLAB = (BKT / 8) * 512;  // bytes of one panel's k-slab
+  static constexpr int CPS = SLAB / 1024;       // 1 KB wave-chunks per slab
+  static constexpr int NCH = (PF + PT) * CPS;
+  static constexpr int LPW = NCH / NW;          // direct-to-LDS loads per wave per stage
+  static constexpr int STAGE = (PF + PT) * SLAB;
+  static constexpr int KS = BKT / 16;
+  static constexpr int LDS_BYTES = NSTAGE * STAGE;
   static_assert(NCH % NW == 0, "chunks must divide over waves");
-  constexpr int LPW = NCH / NW;  // chunk loads per wave per stage
-  constexpr int STAGE = (PF + PT) * SLAB;
+  static_assert((NSTAGE - 2) * LPW <= 63, "vmcnt is 6 bits");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
+};
+
+template <int BF, int BT, int WF, int WT, int BKT, int NSTAGE, int EPI>
+__global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit) {
+  using TL = Tile<BF, BT, WF, WT, BKT, NSTAGE>;
+  constexpr int MI = TL::MI, NJ = TL::NJ, PF = TL::PF, PT = TL::PT, SLAB = TL::SLAB, CPS = TL::CPS;
+  constexpr int LPW = TL::LPW, STAGE = TL::STAGE, KS = TL::KS;
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wf = wave / WT, wt = wave % WT;
 
   // workgroup -> tile.  Consecutive hardware ids go round-robin over the 8 XCDs;
@@ -61,19 +111,18 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   {
     const int per = nblk / 8, rem = nblk % 8;
     const int x = b % 8, i = b / 8;
-    // XCD x owns [x*per + min(x,rem), ...) of the logical order
     b = x * per + (x < rem ? x : rem) + i;
   }
   const int ft = b / nT, tt = b % nT;
   const int Tpanels = (g.T + 31) >> 5;
 
-  const int KT = g.K / BK;
+  const int KT = g.K / BKT;
   const int kt0 = (int)((long)blockIdx.z * KT / ksplit);
   const int kt1 = (int)((long)(blockIdx.z + 1) * KT / ksplit);
+  const int nkt = kt1 - kt0;
 
-  // per-wave chunk sources
+  // per-wave chunk sources (per-lane address); destinations are wave-uniform
   const bf16_t* src[LPW];
-  int dst_off[LPW];
   const size_t krow = (size_t)(g.K >> 3) * 256;  // elements per panel
 #pragma unroll
   for (int c = 0; c < LPW; ++c) {
@@ -84,12 +133,19 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
       base = g.W + (size_t)(ft * PF + q) * krow;
     } else {
       int pnl = tt * PT + (q - PF);
-      pnl = pnl < Tpanels ? pnl : Tpanels - 1;
+      pnl = pnl < Tpanels ? pnl : Tpanels - 1;  // ragged last tile: re-read a real panel
       base = g.X + (size_t)pnl * krow;
     }
-    src[c] = base + sub * 512 + lane * 8;
-    dst_off[c] = ch * 1024 + lane * 16;
+    src[c] = base + (size_t)kt0 * (BKT / 8) * 256 + sub * 512 + lane * 8;
   }
+  auto issue = [&](int i) {  // i: k-tile index relative to kt0
+    unsigned char* dstb = lds + (i % NSTAGE) * STAGE + wave * (LPW * 1024);
+#pragma unroll
+    for (int c = 0; c < LPW; ++c)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[c] + (size_t)i * (BKT / 8) * 256),
+          (__attribute__((address_space(3))) void*)(dstb + c * 1024), 16, 0, 0);
+  };
 
   f32x16 acc[MI][NJ];
 #pragma unroll
@@ -99,42 +155,47 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4 stage_regs[LPW];
-  auto gload = [&](int kt) {
 #pragma unroll
-    for (int c = 0; c < LPW; ++c) stage_regs[c] = *(const u32x4*)(src[c] + (size_t)kt * (BK / 8) * 256);
-  };
-  auto lstore = [&](int buf) {
-#pragma unroll
-    for (int c = 0; c < LPW; ++c) *(u32x4*)(lds + buf * STAGE + dst_off[c]) = stage_regs[c];
-  };
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < nkt) issue(s);
 
-  if (kt0 < kt1) {
-    gload(kt0);
-    lstore(0);
-  }
-  __syncthreads();
+  const uint32_t offW = (wf * MI) * SLAB + lane * 16;
+  const uint32_t offX = (PF + wt * NJ) * SLAB + lane * 16;
 
-  for (int kt = kt0; kt < kt1; ++kt) {
-    const int buf = (kt - kt0) & 1;
-    if (kt + 1 < kt1) gload(kt + 1);
-    const unsigned char* sW = lds + buf * STAGE + (wf * MI) * SLAB + lane * 16;
-    const unsigned char* sX = lds + buf * STAGE + (PF + wt * NJ) * SLAB + lane * 16;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[MI], bb[NJ];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) a[i] = *(const bf16x8*)(sW + i * SLAB + ks * 1024);
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) bb[j] = *(const bf16x8*)(sX + j * SLAB + ks * 1024);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);
+  for (int i = 0; i < nkt; ++i) {
+    // my loads of k-tile i have landed once at most `after` later groups are pending
+    const int after = nkt - 1 - i;
+    if (after >= NSTAGE - 2) {
+      wait_vmcnt<(NSTAGE - 2) * LPW>();
+    } else if (NSTAGE >= 4 && after == NSTAGE - 3) {
+      wait_vmcnt<(NSTAGE >= 4 ? (NSTAGE - 3) * LPW : 0)>();
+    } else if (NSTAGE >= 5 && after == NSTAGE - 4) {
+      wait_vmcnt<(NSTAGE >= 5 ? (NSTAGE - 4) * LPW : 0)>();
+    } else {
+      wait_vmcnt<0>();
     }
-    if (kt + 1 < kt1) lstore(buf ^ 1);
-    __syncthreads();
+    __builtin_amdgcn_s_barrier();  // everyone's loads of tile i landed; everyone finished reading tile i-1
+    if (i + NSTAGE - 1 < nkt) issue(i + NSTAGE - 1);
+
+    const uint32_t sbase = lds_base + (i % NSTAGE) * STAGE;
+    const uint32_t aW = sbase + offW, aX = sbase + offX;
+    bf16x8 a[2][MI], bb[2][NJ];
+    static_for<MI>([&](auto ii) { a[0][ii] = lds_read<ii * SLAB>(aW); });
+    static_for<NJ>([&](auto jj) { bb[0][jj] = lds_read<jj * SLAB>(aX); });
+    static_for<KS>([&](auto ks) {
+      constexpr int cur = ks & 1;
+      wait_operands(a[cur]);
+      wait_operands(bb[cur]);
+      if constexpr (ks + 1 < KS) {
+        static_for<MI>([&](auto ii) { a[cur ^ 1][ii] = lds_read<ii * SLAB + (ks + 1) * 1024>(aW); });
+        static_for<NJ>([&](auto jj) { bb[cur ^ 1][jj] = lds_read<jj * SLAB + (ks + 1) * 1024>(aX); });
+      }
+#pragma unroll
+      for (int ii = 0; ii < MI; ++ii)
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj)
+          acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][ii], bb[cur][jj], acc[ii][jj], 0, 0, 0);
+    });
   }
 
   // ---- epilogue.  lane: token = t0 + 32j + lane%32 ; feature = f0 + 32i + 8*(r/4) + 4*(lane/32) + r%4
@@ -160,21 +221,25 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
         }
       }
     } else if constexpr (EPI == HAT_EPI_SWIGLU) {
-      static_assert(EPI != HAT_EPI_SWIGLU || MI % 2 == 0, "gate/up blocks come in pairs");
+      if constexpr (MI % 2 == 0) {
 #pragma unroll
-      for (int i = 0; i < MI; i += 2) {
-        const int fb = (f_base + i * 32) / 2;  // output feature block
-        if (fb >= g.Nout) continue;
+        for (int i = 0; i < MI; i += 2) {
+          const int fb = (f_base + i * 32) / 2;  // output feature block
+          if (fb >= g.Nout) continue;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int f = fb + 8 * q + 4 * h;
-          bf16x4 v;
+          for (int q = 0; q < 4; ++q) {
+            const int f = fb + 8 * q + 4 * h;
+            bf16x4 v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = (__bf16)(silu_f(acc[i][j][4 * q + e]) * acc[i + 1][j][4 * q + e]);
-          *(bf16x4*)(g.outP + p32_index(tok, f, g.Nout)) = v;
+            for (int e = 0; e < 4; ++e) v[e] = (__bf16)(silu_f(acc[i][j][4 * q + e]) * acc[i + 1][j][4 * q + e]);
+            *(bf16x4*)(g.outP + p32_index(tok, f, g.Nout)) = v;
+          }
         }
       }
     } else {
+      // fp32 result: added into the residual when K is not split, else stored as this
+      // split's partial sum (the next consumer of the residual folds the partials in)
+      float* outb = (ksplit == 1) ? g.resid : g.part + (size_t)blockIdx.z * g.T * g.Nout;
 #pragma unroll
       for (int i = 0; i < MI; ++i) {
         const int fb = f_base + i * 32;
@@ -182,107 +247,125 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int f = fb + 8 * q + 4 * h;
-          float* p = g.resid + (size_t)tok * g.Nout + f;
+          float* p = outb + (size_t)tok * g.Nout + f;
+          f32x4 v;
           if (ksplit == 1) {
-            f32x4 v = *(f32x4*)p;
+            v = *(f32x4*)p;
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] += acc[i][j][4 * q + e];
-            *(f32x4*)p = v;
           } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) atomicAdd(p + e, acc[i][j][4 * q + e]);
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
           }
+          *(f32x4*)p = v;
         }
       }
     }
   }
 }
 
-template <int BF, int BT, int WF, int WT>
-constexpr int lds_bytes() {
-  return 2 * (BF / 32 + BT / 32) * SLAB;
-}
+// tile table: id, features x tokens, waves along features x tokens, k per stage, stages
+#define HAT_FOR_TILES(X, EPI)       \
+  X(0, 256, 256, 2, 2, 64, 2, EPI)  \
+  X(1, 256, 256, 2, 2, 32, 4, EPI)  \
+  X(2, 128, 256, 2, 2, 64, 3, EPI)  \
+  X(3, 256, 128, 2, 2, 64, 3, EPI)  \
+  X(4, 128, 128, 2, 2, 64, 4, EPI)  \
+  X(5, 256, 64, 4, 1, 64, 3, EPI)   \
+  X(6, 256, 32, 4, 1, 64, 4, EPI)   \
+  X(7, 128, 64, 2, 2, 64, 4, EPI)   \
+  X(8, 128, 32, 2, 1, 64, 4, EPI)   \
+  X(9, 64, 256, 1, 4, 64, 3, EPI)
+constexpr int kNumTiles = 10;
 
-template <int BF, int BT, int WF, int WT, int EPI>
-hipError_t launch_cfg(const HatGemm& g, int ksplit, hipStream_t st) {
-  const int nT = (g.T + BT - 1) / BT, nF = g.Nw / BF;
-  dim3 grid(nT * nF, 1, ksplit);
-  constexpr int kLds = lds_bytes<BF, BT, WF, WT>();
-  auto kern = gemm_kernel<BF, BT, WF, WT, EPI>;
-  kern<<<grid, dim3(WF * WT * 64), kLds, st>>>(g, ksplit);
-  return hipGetLastError();
-}
-
-template <int BF, int BT, int WF, int WT, int EPI>
-hipError_t set_attr() {
-  return hipFuncSetAttribute((const void*)gemm_kernel<BF, BT, WF, WT, EPI>,
-                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes<BF, BT, WF, WT>());
-}
-
-// tile shapes: features x tokens, waves along features x waves along tokens
-#define HAT_FOR_TILES(X, EPI) \
-  X(256, 256, 2, 2, EPI)      \
-  X(256, 128, 2, 2, EPI)      \
-  X(256, 64, 4, 1, EPI)       \
-  X(256, 32, 4, 1, EPI)       \
-  X(128, 128, 2, 2, EPI)      \
-  X(128, 64, 2, 2, EPI)       \
-  X(128, 32, 2, 1, EPI)
+struct TileInfo { int bf, bt, waves, mi; };
+constexpr TileInfo kTiles[kNumTiles] = {{256, 256, 4, 4}, {256, 256, 4, 4}, {128, 256, 4, 2}, {256, 128, 4, 4},
+                                        {128, 128, 4, 2}, {256, 64, 4, 2},  {256, 32, 4, 2},  {128, 64, 4, 2},
+                                        {128, 32, 2, 2},  {64, 256, 4, 2}};
 
 template <int EPI>
-hipError_t launch_epi(const HatGemm& g, hipStream_t st) {
-  // Pick the tile (and, where the epilogue accumulates into the fp32 residual,
-  // a K split) with the smallest estimated time: rounds of 256 workgroups times
-  // the work of one workgroup, weighted by how much LDS traffic the wave tile
-  // needs per MFMA.
-  struct Cand { int bf, bt, wf, wt; };
-  static const Cand cands[] = {{256, 256, 2, 2}, {256, 128, 2, 2}, {256, 64, 4, 1}, {256, 32, 4, 1},
-                               {128, 128, 2, 2}, {128, 64, 2, 2},  {128, 32, 2, 1}};
-  const int KT = g.K / BK;
-  double best = 1e300;
-  int bi = 0, bks = 1;
-  for (int c = 0; c < 7; ++c) {
-    const Cand& q = cands[c];
-    const int nT = (g.T + q.bt - 1) / q.bt, nF = g.Nw / q.bf;
-    const int max_split = (EPI == HAT_EPI_RESID) ? 16 : 1;
-    for (int ks = 1; ks <= max_split; ks *= 2) {
-      if (ks > 1 && KT / ks < 4) break;
-      const double rounds = (double)((nT * nF * ks + 255) / 256);
-      const double wtf = q.bf / q.wf, wtt = q.bt / q.wt;
-      const double lds_pen = 1.0 + 24.0 * (1.0 / wtf + 1.0 / wtt);
-      const double waves_pen = (q.wf * q.wt == 4) ? 1.0 : 1.6;  // fewer waves hide less latency
-      const double cost = rounds * ((double)q.bf * q.bt * (KT / ks + 3)) * lds_pen * waves_pen + ks * 1e3;
-      if (cost < best) { best = cost; bi = c; bks = ks; }
-    }
+hipError_t launch_epi(const HatGemm& g, const HatGemmPlan& p, hipStream_t st) {
+#define HAT_TRY(id, bf, bt, wf, wt, bkt, ns, epi)                       \
+  if (p.tile == id) {                                                   \
+    using TL = Tile<bf, bt, wf, wt, bkt, ns>;                           \
+    if (epi == HAT_EPI_SWIGLU && TL::MI % 2 != 0) return hipErrorInvalidValue; \
+    dim3 grid(((g.T + bt - 1) / bt) * (g.Nw / bf), 1, p.ksplit);        \
+    auto kern = gemm_kernel<bf, bt, wf, wt, bkt, ns, epi>;              \
+    kern<<<grid, dim3(wf * wt * 64), TL::LDS_BYTES, st>>>(g, p.ksplit); \
+    return hipGetLastError();                                           \
   }
-  const int BF = cands[bi].bf, BT = cands[bi].bt, ksplit = bks;
-#define HAT_TRY(bf, bt, wf, wt, epi) \
-  if (BF == bf && BT == bt) return launch_cfg<bf, bt, wf, wt, epi>(g, ksplit, st);
   HAT_FOR_TILES(HAT_TRY, EPI)
 #undef HAT_TRY
   return hipErrorInvalidValue;
+}
+
+template <int EPI>
+hipError_t attr_epi() {
+  hipError_t e;
+#define HAT_ATTR(id, bf, bt, wf, wt, bkt, ns, epi)                                                        \
+  e = hipFuncSetAttribute((const void*)gemm_kernel<bf, bt, wf, wt, bkt, ns, epi>,                         \
+                          hipFuncAttributeMaxDynamicSharedMemorySize, Tile<bf, bt, wf, wt, bkt, ns>::LDS_BYTES); \
+  if (e != hipSuccess) return e;
+  HAT_FOR_TILES(HAT_ATTR, EPI)
+#undef HAT_ATTR
+  return hipSuccess;
 }
 
 }  // namespace
 
 hipError_t hat_gemm_init() {
   hipError_t e;
-#define HAT_ATTR(bf, bt, wf, wt, epi) \
-  if ((e = set_attr<bf, bt, wf, wt, epi>()) != hipSuccess) return e;
-  HAT_FOR_TILES(HAT_ATTR, HAT_EPI_P32)
-  HAT_FOR_TILES(HAT_ATTR, HAT_EPI_SWIGLU)
-  HAT_FOR_TILES(HAT_ATTR, HAT_EPI_RESID)
-#undef HAT_ATTR
+  if ((e = attr_epi<HAT_EPI_P32>()) != hipSuccess) return e;
+  if ((e = attr_epi<HAT_EPI_SWIGLU>()) != hipSuccess) return e;
+  if ((e = attr_epi<HAT_EPI_RESID>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
-hipError_t hat_launch_gemm(const HatGemm& g, hipStream_t st) {
+HatGemmPlan hat_gemm_plan(const HatGemm& g) {
+  // Estimated time of a candidate = rounds of 256 workgroups x the larger of the
+  // MFMA time and the L2->LDS streaming time of one workgroup; split-K (only where
+  // the result is accumulated in fp32) adds the traffic of its partial sums.
+  HatGemmPlan best{0, 1};
+  if (g.force_tile >= 0 && g.force_tile < kNumTiles) {
+    best.tile = g.force_tile;
+    best.ksplit = g.force_ksplit > 0 ? g.force_ksplit : 1;
+    if (g.epilogue != HAT_EPI_RESID || !g.part) best.ksplit = 1;
+    while (best.ksplit > 1 && ((long)best.ksplit * g.T > g.part_rows || g.K / 64 / best.ksplit < 1)) --best.ksplit;
+    if (g.epilogue == HAT_EPI_SWIGLU && kTiles[best.tile].mi % 2 != 0) best.tile = 0;
+    return best;
+  }
+  double best_cost = 1e300;
+  const int KT = g.K / 64;
+  for (int c = 0; c < kNumTiles; ++c) {
+    if (c == 1) continue;  // alternative staging of tile 0, selected only when forced
+    const TileInfo& q = kTiles[c];
+    if (g.epilogue == HAT_EPI_SWIGLU && q.mi % 2 != 0) continue;
+    const int nT = (g.T + q.bt - 1) / q.bt, nF = g.Nw / q.bf;
+    const int max_split = (g.epilogue == HAT_EPI_RESID && g.part) ? 16 : 1;
+    for (int ks = 1; ks <= max_split; ++ks) {
+      if (ks > 1 && (KT / ks < 4 || (long)ks * g.T > g.part_rows)) break;
+      const double blocks = (double)nT * nF * ks;
+      const double rounds = std::ceil(blocks / 256.0);
+      const double kt = std::ceil((double)KT / ks) + 2.0;              // + pipeline fill
+      const double mfma_cyc = 2.0 * q.bf * q.bt * 64 / (4 * 1017.0);   // per k-tile, 4 SIMDs
+      const double load_cyc = (q.bf + q.bt) * 64 * 2 / 48.0;           // per k-tile at ~48 B/clk/CU
+      double cost = rounds * kt * std::max(mfma_cyc, load_cyc) * (q.waves == 4 ? 1.0 : 1.5);
+      cost += rounds * 1500.0;                                          // launch/epilogue per round
+      if (ks > 1) cost += (double)ks * g.T * g.Nout * 8.0 / 256.0 / 32.0;  // partial write+read, per CU
+      if (cost < best_cost) { best_cost = cost; best.tile = c; best.ksplit = ks; }
+    }
+  }
+  return best;
+}
+
+hipError_t hat_launch_gemm(const HatGemm& g, const HatGemmPlan& p, hipStream_t st) {
   if (g.T <= 0) return hipSuccess;
-  if (g.K % BK != 0 || g.Nw % 256 != 0) return hipErrorInvalidValue;
+  if (g.K % 64 != 0 || g.Nw % 256 != 0) return hipErrorInvalidValue;
+  if (p.ksplit > 1 && (g.epilogue != HAT_EPI_RESID || !g.part)) return hipErrorInvalidValue;
   switch (g.epilogue) {
-    case HAT_EPI_P32: return launch_epi<HAT_EPI_P32>(g, st);
-    case HAT_EPI_SWIGLU: return launch_epi<HAT_EPI_SWIGLU>(g, st);
-    case HAT_EPI_RESID: return launch_epi<HAT_EPI_RESID>(g, st);
+    case HAT_EPI_P32: return launch_epi<HAT_EPI_P32>(g, p, st);
+    case HAT_EPI_SWIGLU: return launch_epi<HAT_EPI_SWIGLU>(g, p, st);
+    case HAT_EPI_RESID: return launch_epi<HAT_EPI_RESID>(g, p, st);
   }
   return hipErrorInvalidValue;
 }

@@ -24,10 +24,19 @@ struct HatGemm {
   int Nw;           // rows of W including padding
   int Nout;         // logical output features (EPI_SWIGLU: Nw/2 >= Nout)
   bf16_t* outP;     // EPI_P32 / EPI_SWIGLU
-  float* resid;     // EPI_RESID
+  float* resid;     // EPI_RESID, K not split: resid[t, f] += result
+  float* part;      // EPI_RESID, K split s ways: part[z][t][f] = partial sum of split z (may be null: no split)
+  int part_rows;    // capacity of `part` in rows of Nout floats (bounds ksplit * T)
   int epilogue;
+  int force_tile;   // >= 0: use this tile id (tuning); -1: choose
+  int force_ksplit; // with force_tile: K split (0/1 = none)
 };
-hipError_t hat_launch_gemm(const HatGemm& g, hipStream_t st);
+struct HatGemmPlan {
+  int tile;    // index into the tile table of gemm.hip
+  int ksplit;  // 1 = K not split
+};
+HatGemmPlan hat_gemm_plan(const HatGemm& g);
+hipError_t hat_launch_gemm(const HatGemm& g, const HatGemmPlan& p, hipStream_t st);
 hipError_t hat_gemm_init();  // one-time function attributes (dynamic LDS size)
 
 // ---- weight re-tiling (create time) -----------------------------------------
@@ -54,10 +63,13 @@ struct HatPlanDev {
 };
 
 hipError_t hat_launch_gather(const HatPlanDev& p, float* resid, int d, int io_dtype, hipStream_t st);
-hipError_t hat_launch_scatter(const HatPlanDev& p, const float* resid, int d, int io_dtype, hipStream_t st);
+hipError_t hat_launch_scatter(const HatPlanDev& p, const float* resid, const float* part, int nparts, int d,
+                              int io_dtype, hipStream_t st);
 hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, float2* table, int half, hipStream_t st);
-hipError_t hat_launch_rmsnorm(const float* resid, const float* gain, bf16_t* outP, int T, int d, float eps,
-                              hipStream_t st);
+// x = resid + sum of nparts partial sums (part[i][t][:], stride T*d); if nparts > 0 the sum is
+// written back to resid.  out = rmsnorm(x) * gain as bf16 in P32 layout.
+hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, bf16_t* outP, int T,
+                              int d, float eps, hipStream_t st);
 // qkv: P32 [., 3d]; rotates q in place, writes rotated k and v into the pool of one layer
 hipError_t hat_launch_rope_append(const HatPlanDev& p, bf16_t* qkv, const float2* table, bf16_t* pool_layer,
                                   int H, int hd, hipStream_t st);
