@@ -122,11 +122,15 @@ class OracleMiddle:
         self.cfg = dict(cfg)
         self.dtype = dtype
         self._layers = layers
+        self._converted = {}    # layers given as a list are widened to `dtype` once
         self.kv = {}            # device -> list over layers of [K, V]
 
     def _layer(self, l):
-        w = self._layers(l) if callable(self._layers) else self._layers[l]
-        return {k: np.asarray(v, dtype=self.dtype) for k, v in w.items()}
+        if callable(self._layers):
+            return {k: np.asarray(v, dtype=self.dtype) for k, v in self._layers(l).items()}
+        if l not in self._converted:
+            self._converted[l] = {k: np.asarray(v, dtype=self.dtype) for k, v in self._layers[l].items()}
+        return self._converted[l]
 
     def kv_len(self, device):
         if device not in self.kv:

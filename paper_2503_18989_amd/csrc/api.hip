@@ -24,7 +24,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
 
 struct LayerDev {
-  bf16_t *wqkv, *wo, *wgu, *wd;
+  act_t *wqkv, *wo, *wgu, *wd;
   float *g_attn, *g_ffn;
 };
 
@@ -65,11 +65,11 @@ Shapes make_shapes(const hat_mid_config_t& c) {
   const int per_head = (s.attn_target + s.H - 1) / s.H;
   s.chunk_items_cap = 2 * per_head + s.Tcap / 128 + c.max_devices + 2;
   s.verify_items_cap = 2 * per_head + c.max_devices + 2;
-  s.merge_cap = s.Tcap / 128 + 2 * c.max_devices + 2;
+  s.merge_cap = s.Tcap / 16 + s.Tcap / 128 + 2 * c.max_devices + 2;
   s.part_rows_cap = 128 * (2 * per_head + 2) + HAT_MAX_VERIFY * s.verify_items_cap;
   s.gemm_part_rows = 4096;
   s.plan_words = (size_t)3 * s.Tcap + 8 * (size_t)c.max_devices + 16 + (size_t)c.n_pages + c.max_devices +
-                 8 * ((size_t)s.chunk_items_cap + s.verify_items_cap) + 4 * (size_t)s.merge_cap + 64;
+                 8 * ((size_t)s.chunk_items_cap + s.verify_items_cap) + 8 * (size_t)s.merge_cap + 64;
   return s;
 }
 
@@ -91,7 +91,7 @@ struct Buffers {
   std::vector<LayerDev> layers;
   double* inv_freq;
   float* resid;
-  bf16_t *xn, *xn2, *qkv, *attn, *act;
+  act_t *xn, *xn2, *qkv, *attn, *act;
   float2* table;
   float* part_o;
   float2* part_ml;
@@ -105,20 +105,20 @@ size_t carve(const hat_mid_config_t& c, const Shapes& s, void* base, Buffers* ou
   Buffers b;
   b.layers.resize(s.L);
   for (int l = 0; l < s.L; ++l) {
-    b.layers[l].wqkv = cv.take<bf16_t>((size_t)s.Nqkv * s.d);
-    b.layers[l].wo = cv.take<bf16_t>((size_t)s.No * s.d);
-    b.layers[l].wgu = cv.take<bf16_t>((size_t)s.Ngu * s.d);
-    b.layers[l].wd = cv.take<bf16_t>((size_t)s.Nd * s.Fpad);
+    b.layers[l].wqkv = cv.take<act_t>((size_t)s.Nqkv * s.d);
+    b.layers[l].wo = cv.take<act_t>((size_t)s.No * s.d);
+    b.layers[l].wgu = cv.take<act_t>((size_t)s.Ngu * s.d);
+    b.layers[l].wd = cv.take<act_t>((size_t)s.Nd * s.Fpad);
     b.layers[l].g_attn = cv.take<float>(s.d);
     b.layers[l].g_ffn = cv.take<float>(s.d);
   }
   b.inv_freq = cv.take<double>(s.hd / 2);
   b.resid = cv.take<float>((size_t)s.Tcap * s.d);
-  b.xn = cv.take<bf16_t>((size_t)s.Tcap * s.d);
-  b.xn2 = cv.take<bf16_t>((size_t)s.Tcap * s.d);
-  b.qkv = cv.take<bf16_t>((size_t)s.Tcap * 3 * s.d);
-  b.attn = cv.take<bf16_t>((size_t)s.Tcap * s.d);
-  b.act = cv.take<bf16_t>((size_t)s.Tcap * s.Fpad);
+  b.xn = cv.take<act_t>((size_t)s.Tcap * s.d);
+  b.xn2 = cv.take<act_t>((size_t)s.Tcap * s.d);
+  b.qkv = cv.take<act_t>((size_t)s.Tcap * 3 * s.d);
+  b.attn = cv.take<act_t>((size_t)s.Tcap * s.d);
+  b.act = cv.take<act_t>((size_t)s.Tcap * s.Fpad);
   b.table = cv.take<float2>((size_t)s.Tcap * (s.hd / 2));
   b.part_o = cv.take<float>((size_t)s.part_rows_cap * s.d);
   b.part_ml = cv.take<float2>((size_t)s.part_rows_cap * s.H);
@@ -470,6 +470,15 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
   {
     const int per_head = (s.attn_target + s.H - 1) / s.H;  // items wanted
     int part_row = 0;
+    // rows of a split item are merged in groups of 16 (one workgroup per group and head)
+    auto push_merge = [&](int row0, int nrows, int prow, int nsplit) {
+      for (int g0 = 0; g0 < nrows; g0 += 16) {
+        HatMergeItem m{};
+        m.row0 = row0 + g0; m.nrows = std::min(16, nrows - g0); m.part_row = prow + g0; m.nsplit = nsplit;
+        m.stride = nrows;
+        mitems.push_back(m);
+      }
+    };
     // verify segments: split each cache into key ranges of about equal size
     long vkeys = 0;
     int nver = 0;
@@ -486,7 +495,6 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
         if ((int)vitems.size() + ns > s.verify_items_cap - 1 || part_row + ns * segs[i].n > s.part_rows_cap) ns = 1;
         const int step = round_up((len + ns - 1) / ns, 64);
         ns = (len + step - 1) / step;
-        HatMergeItem m{P[o_toff + i], segs[i].n, part_row, ns};
         for (int k = 0; k < ns; ++k) {
           HatAttnItem it{};
           it.seg = i; it.q0 = 0; it.nq = segs[i].n;
@@ -495,7 +503,7 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
           vitems.push_back(it);
         }
         if (ns > 1) {
-          mitems.push_back(m);
+          push_merge(P[o_toff + i], segs[i].n, part_row, ns);
           part_row += ns * segs[i].n;
         }
       }
@@ -513,11 +521,10 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
           const int need = segs[i].start_pos + q0 + nq;
           int ns = std::min(std::min(want, std::max(1, need / 256)), 16);
           if ((int)citems.size() + ns > s.chunk_items_cap - 1 || part_row + ns * nq > s.part_rows_cap ||
-              (int)mitems.size() >= s.merge_cap - 1)
+              (int)mitems.size() + 9 >= s.merge_cap)
             ns = 1;
           const int step = round_up((need + ns - 1) / ns, 64);
           ns = (need + step - 1) / step;
-          HatMergeItem m{P[o_toff + i] + q0, nq, part_row, ns};
           for (int k = 0; k < ns; ++k) {
             HatAttnItem it{};
             it.seg = i; it.q0 = q0; it.nq = nq;
@@ -526,7 +533,7 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
             citems.push_back(it);
           }
           if (ns > 1) {
-            mitems.push_back(m);
+            push_merge(P[o_toff + i] + q0, nq, part_row, ns);
             part_row += ns * nq;
           }
         }
@@ -538,9 +545,9 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
     std::stable_sort(citems.begin(), citems.end(), by_cost);
     std::stable_sort(vitems.begin(), vitems.end(), by_cost);
   }
-  const size_t o_ci = take(8 * citems.size(), 8), o_vi = take(8 * vitems.size(), 8), o_mi = take(4 * mitems.size(), 4);
+  const size_t o_ci = take(8 * citems.size(), 8), o_vi = take(8 * vitems.size(), 8), o_mi = take(8 * mitems.size(), 8);
   if (w > s.plan_words) return fail(h, HAT_EINVAL, "internal: plan of %zu words exceeds capacity %zu", w, s.plan_words);
-  static_assert(sizeof(HatAttnItem) == 32 && sizeof(HatMergeItem) == 16, "plan item sizes");
+  static_assert(sizeof(HatAttnItem) == 32 && sizeof(HatMergeItem) == 32, "plan item sizes");
   if (!citems.empty()) memcpy(&P[o_ci], citems.data(), citems.size() * sizeof(HatAttnItem));
   if (!vitems.empty()) memcpy(&P[o_vi], vitems.data(), vitems.size() * sizeof(HatAttnItem));
   if (!mitems.empty()) memcpy(&P[o_mi], mitems.data(), mitems.size() * sizeof(HatMergeItem));

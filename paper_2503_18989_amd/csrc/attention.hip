@@ -12,7 +12,10 @@
 //             so a wave instruction reads whole contiguous 512 B / 1 KB runs),
 //             then the four waves' partial results are merged through LDS.
 //
-// Both compute S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so a lane owns ONE query
+// The cache holds bf16; queries, probabilities and outputs are fp16 like every other
+// activation, so K and V are widened bf16 -> fp16 in registers (exact for
+// magnitudes in [2^-17, 65504], saturating above) on their way to the MFMA.
+// Both compute S^T = K Q^T with v_mfma_f32_32x32x16_f16, so a lane owns ONE query
 // column and 16 keys of it: the online softmax is lane-local except for one
 // exchange between the two lane halves, and the probabilities are already in the
 // B-operand order of O^T += V^T P^T (the V tile is stored in that key order).
@@ -24,8 +27,9 @@
 #include "hat_kernels.h"
 #include "hat_layout.h"
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -55,7 +59,7 @@ __device__ __forceinline__ SegInfo seg_info(const HatPlanDev& p, int seg) {
 // two B operands (keys 0..15 / 16..31 of the tile) and rescales O.
 template <int NC>
 __device__ __forceinline__ void softmax_step(const f32x16& s_acc, float scale_log2, int key0, int half, int qpos,
-                                             float& m_run, float& l_run, f32x16 (&o)[NC], bf16x8& p0, bf16x8& p1) {
+                                             float& m_run, float& l_run, f32x16 (&o)[NC], f16x8& p0, f16x8& p1) {
   float sl[16];
   float mx = -INFINITY;
 #pragma unroll
@@ -83,21 +87,37 @@ __device__ __forceinline__ void softmax_step(const f32x16& s_acc, float scale_lo
     for (int r = 0; r < 16; ++r) o[c][r] *= alpha;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    p0[j] = (__bf16)pv[j];
-    p1[j] = (__bf16)pv[8 + j];
+    p0[j] = (_Float16)pv[j];
+    p1[j] = (_Float16)pv[8 + j];
   }
 }
 
 // zero the V operand elements whose key lies at or beyond kv_len (stale memory
 // there may hold NaN patterns, and 0 * NaN would poison the accumulator)
-__device__ __forceinline__ bf16x8 clean_v(bf16x8 v, int page_key0, int half, int kv_len) {
+__device__ __forceinline__ f16x8 clean_v(f16x8 v, int page_key0, int half, int kv_len) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int key = page_key0 + 8 * (j >> 2) + 4 * half + (j & 3);
-    if (key >= kv_len) v[j] = (__bf16)0.f;
+    if (key >= kv_len) v[j] = (_Float16)0.f;
   }
   return v;
 }
+
+// 8 bf16 (as loaded from the cache) -> 8 fp16.  bf16 -> fp32 is a shift; fp32 -> fp16
+// with round-toward-zero is exact where the value is representable and saturates
+// (instead of overflowing to infinity) where it is not.
+__device__ __forceinline__ u32x4 kv_to_f16_bits(u32x4 raw) {
+  u32x4 out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = __uint_as_float(raw[i] << 16), hi = __uint_as_float(raw[i] & 0xffff0000u);
+    out[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+  }
+  return out;
+}
+__device__ __forceinline__ f16x8 kv_to_f16(u32x4 raw) { return __builtin_bit_cast(f16x8, kv_to_f16_bits(raw)); }
+
+__device__ __forceinline__ _Float16 to_act(float x) { return (_Float16)__builtin_amdgcn_fmed3f(x, -65504.f, 65504.f); }
 
 // ------------------------------------------------------------------ verify
 template <int HD>
@@ -118,10 +138,10 @@ __global__ __launch_bounds__(256) void attn_verify_kernel(HatPlanDev p, HatAttn 
   const int qpos = sg.start + it.q0 + qi;
   const float scale_log2 = kLog2e / sqrtf((float)HD);
 
-  bf16x8 qreg[NS];
+  f16x8 qreg[NS];
 #pragma unroll
   for (int s = 0; s < NS; ++s)
-    qreg[s] = *(const bf16x8*)(a.qkv + p32_index(qrow, head * HD + (2 * s + half) * 8, 3 * a.d));
+    qreg[s] = *(const f16x8*)(a.qkv + p32_index(qrow, head * HD + (2 * s + half) * 8, 3 * a.d));
 
   f32x16 o[NC];
 #pragma unroll
@@ -142,19 +162,27 @@ __global__ __launch_bounds__(256) void attn_verify_kernel(HatPlanDev p, HatAttn 
     const bf16_t* recA = pool + (size_t)sg.pt[ia] * page_stride;
     const bf16_t* recB = pool + (size_t)sg.pt[ib] * page_stride;
     const bf16_t* krec = (n < 16) ? recA : recB;
-    bf16x8 kreg[NS], va[NC], vb[NC];
+    u32x4 kraw[NS], varaw[NC], vbraw[NC];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) kreg[s] = *(const bf16x8*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8);
+    for (int s = 0; s < NS; ++s) kraw[s] = *(const u32x4*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8);
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      va[c] = *(const bf16x8*)(recA + 16 * HD + c * 512 + lane * 8);
-      vb[c] = *(const bf16x8*)(recB + 16 * HD + c * 512 + lane * 8);
+      varaw[c] = *(const u32x4*)(recA + 16 * HD + c * 512 + lane * 8);
+      vbraw[c] = *(const u32x4*)(recB + 16 * HD + c * 512 + lane * 8);
+    }
+    f16x8 kreg[NS], va[NC], vb[NC];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) kreg[s] = kv_to_f16(kraw[s]);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      va[c] = kv_to_f16(varaw[c]);
+      vb[c] = kv_to_f16(vbraw[c]);
     }
     f32x16 sacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[s], qreg[s], sacc, 0, 0, 0);
+    for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[s], qreg[s], sacc, 0, 0, 0);
     if (key0 + 32 > sg.kv_len) {
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
@@ -162,12 +190,12 @@ __global__ __launch_bounds__(256) void attn_verify_kernel(HatPlanDev p, HatAttn 
         vb[c] = clean_v(vb[c], key0 + 16, half, sg.kv_len);
       }
     }
-    bf16x8 p0, p1;
+    f16x8 p0, p1;
     softmax_step<NC>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[c], p0, o[c], 0, 0, 0);
-      o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[c], p1, o[c], 0, 0, 0);
+      o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[c], p0, o[c], 0, 0, 0);
+      o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb[c], p1, o[c], 0, 0, 0);
     }
   }
   l_run += __shfl_xor(l_run, 32);
@@ -200,10 +228,10 @@ __global__ __launch_bounds__(256) void attn_verify_kernel(HatPlanDev p, HatAttn 
     }
     if (it.part_row < 0) {
       const float inv = 1.0f / L;
-      bf16x4 ov;
+      f16x4 ov;
 #pragma unroll
-      for (int x = 0; x < 4; ++x) ov[x] = (__bf16)(acc[x] * inv);
-      *(bf16x4*)(a.outP + p32_index(sg.tok0 + it.q0 + q, head * HD + e, a.d)) = ov;
+      for (int x = 0; x < 4; ++x) ov[x] = to_act(acc[x] * inv);
+      *(f16x4*)(a.outP + p32_index(sg.tok0 + it.q0 + q, head * HD + e, a.d)) = ov;
     } else {
       const size_t pr = (size_t)(it.part_row + q) * a.H + head;
       *(f32x4*)(a.part_o + pr * HD + e) = acc;
@@ -238,10 +266,10 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a
   const int wave_last_pos = wave_live ? sg.start + wq0 + nq_w - 1 : -1;
   const float scale_log2 = kLog2e / sqrtf((float)HD);
 
-  bf16x8 qreg[NS];
+  f16x8 qreg[NS];
 #pragma unroll
   for (int s = 0; s < NS; ++s)
-    qreg[s] = *(const bf16x8*)(a.qkv + p32_index(qrow, head * HD + (2 * s + half) * 8, 3 * a.d));
+    qreg[s] = *(const f16x8*)(a.qkv + p32_index(qrow, head * HD + (2 * s + half) * 8, 3 * a.d));
 
   f32x16 o[NC];
 #pragma unroll
@@ -271,10 +299,10 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a
   };
   auto lstore = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * 256 + threadIdx.x) * 16]) = regs[i];
+    for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * 256 + threadIdx.x) * 16]) = kv_to_f16_bits(regs[i]);
   };
 
-  if (st0 < st1) {
+  if (st0 < st1) {  // tiles are widened to fp16 once, on their way into LDS
     gload(st0);
     lstore(0);
   }
@@ -295,22 +323,22 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a
       for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        const bf16x8 kk = *(const bf16x8*)(krec + ((2 * s + half) * 16 + (n & 15)) * 16);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk, qreg[s], sacc, 0, 0, 0);
+        const f16x8 kk = *(const f16x8*)(krec + ((2 * s + half) * 16 + (n & 15)) * 16);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kk, qreg[s], sacc, 0, 0, 0);
       }
-      bf16x8 p0, p1;
+      f16x8 p0, p1;
       softmax_step<NC>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
       const bool tail = key0 + 32 > sg.kv_len;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        bf16x8 va = *(const bf16x8*)(recA + 16 * HD * 2 + c * 1024 + lane * 16);
-        bf16x8 vb = *(const bf16x8*)(recB + 16 * HD * 2 + c * 1024 + lane * 16);
+        f16x8 va = *(const f16x8*)(recA + 16 * HD * 2 + c * 1024 + lane * 16);
+        f16x8 vb = *(const f16x8*)(recB + 16 * HD * 2 + c * 1024 + lane * 16);
         if (tail) {
           va = clean_v(va, key0, half, sg.kv_len);
           vb = clean_v(vb, key0 + 16, half, sg.kv_len);
         }
-        o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, p0, o[c], 0, 0, 0);
-        o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, p1, o[c], 0, 0, 0);
+        o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, p0, o[c], 0, 0, 0);
+        o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb, p1, o[c], 0, 0, 0);
       }
     }
     if (st + 1 < st1) lstore(buf ^ 1);
@@ -326,10 +354,10 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a
       for (int c = 0; c < NC; ++c)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          bf16x4 ov;
+          f16x4 ov;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(o[c][4 * g + e] * inv);
-          *(bf16x4*)(a.outP + p32_index(sg.tok0 + row, head * HD + 32 * c + 8 * g + 4 * half, a.d)) = ov;
+          for (int e = 0; e < 4; ++e) ov[e] = to_act(o[c][4 * g + e] * inv);
+          *(f16x4*)(a.outP + p32_index(sg.tok0 + row, head * HD + 32 * c + 8 * g + 4 * half, a.d)) = ov;
         }
     } else {
       const size_t prow = (size_t)(it.part_row + 32 * wave + n) * a.H + head;
@@ -348,20 +376,20 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a
 }
 
 // ------------------------------------------------------------------ merge
-// one thread per (row, head, 8 output features)
+// one workgroup per (group of <= 16 rows, head); one thread per (row, 8 features)
 template <int HD>
-__global__ void attn_merge_kernel(HatAttn a, const HatMergeItem* __restrict__ items) {
+__global__ __launch_bounds__(256) void attn_merge_kernel(HatAttn a, const HatMergeItem* __restrict__ items) {
   const HatMergeItem it = items[blockIdx.x];
   const int head = blockIdx.y;
-  for (int idx = threadIdx.x; idx < it.nrows * (HD / 8); idx += blockDim.x) {
+  for (int idx = threadIdx.x; idx < it.nrows * (HD / 8); idx += 256) {
     const int r = idx / (HD / 8), e = (idx % (HD / 8)) * 8;
     float M = -INFINITY;
     for (int s = 0; s < it.nsplit; ++s)
-      M = fmaxf(M, a.part_ml[(size_t)(it.part_row + s * it.nrows + r) * a.H + head].x);
+      M = fmaxf(M, a.part_ml[(size_t)(it.part_row + s * it.stride + r) * a.H + head].x);
     float L = 0.f;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int s = 0; s < it.nsplit; ++s) {
-      const size_t pr = (size_t)(it.part_row + s * it.nrows + r) * a.H + head;
+      const size_t pr = (size_t)(it.part_row + s * it.stride + r) * a.H + head;
       const float2 ml = a.part_ml[pr];
       const float f = exp2f(ml.x - M);
       L += ml.y * f;
@@ -373,10 +401,10 @@ __global__ void attn_merge_kernel(HatAttn a, const HatMergeItem* __restrict__ it
       }
     }
     const float inv = 1.0f / L;
-    bf16x8 ov;
+    f16x8 ov;
 #pragma unroll
-    for (int x = 0; x < 8; ++x) ov[x] = (__bf16)(acc[x] * inv);
-    *(bf16x8*)(a.outP + p32_index(it.row0 + r, head * HD + e, a.d)) = ov;
+    for (int x = 0; x < 8; ++x) ov[x] = to_act(acc[x] * inv);
+    *(f16x8*)(a.outP + p32_index(it.row0 + r, head * HD + e, a.d)) = ov;
   }
 }
 

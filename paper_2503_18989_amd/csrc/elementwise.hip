@@ -9,6 +9,10 @@
 #include "hat_layout.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// fp32 -> fp16, round to nearest even, saturating instead of overflowing to infinity
+__device__ __forceinline__ _Float16 to_act(float x) { return (_Float16)__builtin_amdgcn_fmed3f(x, -65504.f, 65504.f); }
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
@@ -80,11 +84,11 @@ __global__ void rope_table_kernel(HatPlanDev p, const double* __restrict__ inv_f
 
 // ---------------------------------------------------------------- RMSNorm
 // one workgroup (256 threads) per row: x = resid + pending split-K partial sums
-// (written back), y = x * rsqrt(mean(x^2) + eps) * gain as bf16 in P32 layout.
+// (written back), y = x * rsqrt(mean(x^2) + eps) * gain as fp16 in P32 layout.
 // A row (<= 8192 floats) stays in registers between the two passes.
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ resid, const float* __restrict__ part,
                                                        int nparts, int T, const float* __restrict__ gain,
-                                                       bf16_t* __restrict__ outP, int d, float eps) {
+                                                       act_t* __restrict__ outP, int d, float eps) {
   const int t = blockIdx.x;
   float* x = resid + (size_t)t * d;
   const size_t pstride = (size_t)T * d;
@@ -120,19 +124,19 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ resid,
     const int i = (v * 256 + threadIdx.x) * 8;
     if (i < d) {
       const f32x4 ga = *(const f32x4*)(gain + i), gb = *(const f32x4*)(gain + i + 4);
-      bf16x8 o;
+      f16x8 o;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { o[e] = (__bf16)(va[v][e] * r * ga[e]); o[4 + e] = (__bf16)(vb[v][e] * r * gb[e]); }
-      *(bf16x8*)(outP + p32_index(t, i, d)) = o;
+      for (int e = 0; e < 4; ++e) { o[e] = to_act(va[v][e] * r * ga[e]); o[4 + e] = to_act(vb[v][e] * r * gb[e]); }
+      *(f16x8*)(outP + p32_index(t, i, d)) = o;
     }
   }
 }
 
 // ---------------------------------------------------------------- RoPE + KV append
 // One thread per (row, head, octet pair): octets o and o + hd/16 hold the two
-// halves of 8 rotation pairs.  q is rotated in place; rotated k and v go to the
-// row's (page, slot) of this layer's pool.
-__global__ void rope_append_kernel(HatPlanDev p, bf16_t* __restrict__ qkv, const float2* __restrict__ table,
+// halves of 8 rotation pairs.  q is rotated in place (fp16); rotated k and v are
+// rounded to bf16 and go to the row's (page, slot) of this layer's pool.
+__global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const float2* __restrict__ table,
                                    bf16_t* __restrict__ pool, int H, int hd) {
   const int half_oct = hd >> 4;                 // octets per half head
   const int per_row = H * half_oct;
@@ -144,26 +148,27 @@ __global__ void rope_append_kernel(HatPlanDev p, bf16_t* __restrict__ qkv, const
   const int c_lo = hh * hd + o * 8, c_hi = c_lo + (hd >> 1);
   const float2* cs = table + (size_t)t * (hd >> 1) + o * 8;
 
-  bf16_t* q_lo = qkv + p32_index(t, c_lo, row_len);
-  bf16_t* q_hi = qkv + p32_index(t, c_hi, row_len);
-  const bf16x8 ql = *(bf16x8*)q_lo, qh = *(bf16x8*)q_hi;
-  const bf16x8 kl = *(const bf16x8*)(qkv + p32_index(t, d + c_lo, row_len));
-  const bf16x8 kh = *(const bf16x8*)(qkv + p32_index(t, d + c_hi, row_len));
-  const bf16x8 vl = *(const bf16x8*)(qkv + p32_index(t, 2 * d + c_lo, row_len));
-  const bf16x8 vh = *(const bf16x8*)(qkv + p32_index(t, 2 * d + c_hi, row_len));
-  bf16x8 rql, rqh, rkl, rkh;
+  act_t* q_lo = qkv + p32_index(t, c_lo, row_len);
+  act_t* q_hi = qkv + p32_index(t, c_hi, row_len);
+  const f16x8 ql = *(f16x8*)q_lo, qh = *(f16x8*)q_hi;
+  const f16x8 kl = *(const f16x8*)(qkv + p32_index(t, d + c_lo, row_len));
+  const f16x8 kh = *(const f16x8*)(qkv + p32_index(t, d + c_hi, row_len));
+  const f16x8 vl = *(const f16x8*)(qkv + p32_index(t, 2 * d + c_lo, row_len));
+  const f16x8 vh = *(const f16x8*)(qkv + p32_index(t, 2 * d + c_hi, row_len));
+  f16x8 rql, rqh;
+  bf16x8 rkl, rkh;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const float c = cs[e].x, s = cs[e].y;
     const float a = (float)ql[e], b = (float)qh[e];
-    rql[e] = (__bf16)(a * c - b * s);
-    rqh[e] = (__bf16)(b * c + a * s);
+    rql[e] = to_act(a * c - b * s);
+    rqh[e] = to_act(b * c + a * s);
     const float ka = (float)kl[e], kb = (float)kh[e];
     rkl[e] = (__bf16)(ka * c - kb * s);
     rkh[e] = (__bf16)(kb * c + ka * s);
   }
-  *(bf16x8*)q_lo = rql;
-  *(bf16x8*)q_hi = rqh;
+  *(f16x8*)q_lo = rql;
+  *(f16x8*)q_hi = rqh;
 
   const int dst = p.kv_dst[t];
   const int page = dst >> 4, slot = dst & 15;
@@ -173,13 +178,13 @@ __global__ void rope_append_kernel(HatPlanDev p, bf16_t* __restrict__ qkv, const
   *(bf16x8*)(kt + ktile_index(slot, o * 8 + (hd >> 1))) = rkh;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    vt[vtile_index(slot, o * 8 + e)] = vl[e];
-    vt[vtile_index(slot, o * 8 + (hd >> 1) + e)] = vh[e];
+    vt[vtile_index(slot, o * 8 + e)] = (__bf16)(float)vl[e];
+    vt[vtile_index(slot, o * 8 + (hd >> 1) + e)] = (__bf16)(float)vh[e];
   }
 }
 
 // ---------------------------------------------------------------- weight re-tiling
-__global__ void retile_kernel(bf16_t* __restrict__ dst, int Nw, int Kd, const bf16_t* __restrict__ s0,
+__global__ void retile_kernel(act_t* __restrict__ dst, int Nw, int Kd, const bf16_t* __restrict__ s0,
                               const bf16_t* __restrict__ s1, const bf16_t* __restrict__ s2, int n0, int Ks, int mode) {
   // one thread per destination octet
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -219,7 +224,12 @@ __global__ void retile_kernel(bf16_t* __restrict__ dst, int Nw, int Kd, const bf
         if (k + e < Ks) v[e] = src[(size_t)sr * Ks + k + e];
     }
   }
-  *(bf16x8*)(dst + idx * 8) = v;
+  // bf16 -> fp16 through fp32: exact for |w| in [2^-17, 65504] (8 mantissa bits fit in 11);
+  // smaller magnitudes keep an absolute error below 2^-25, larger ones saturate
+  f16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = to_act((float)v[e]);
+  *(f16x8*)(dst + idx * 8) = o;
 }
 
 __global__ void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, int n) {
@@ -268,7 +278,7 @@ __global__ void kv_export_kernel(const bf16_t* __restrict__ pool, const int32_t*
   *(bf16x8*)(v + so) = vv;
 }
 
-__global__ void unpack_p32_kernel(const bf16_t* __restrict__ srcP, int row_len, int col0, int ncols, int T,
+__global__ void unpack_p32_kernel(const act_t* __restrict__ srcP, int row_len, int col0, int ncols, int T,
                                   float* __restrict__ dst) {
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)T * ncols) return;
@@ -294,19 +304,19 @@ hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, fl
   rope_table_kernel<<<blocks_for((size_t)p.T * half, 256), 256, 0, st>>>(p, inv_freq, table, half);
   return hipGetLastError();
 }
-hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, bf16_t* outP, int T,
+hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, act_t* outP, int T,
                               int d, float eps, hipStream_t st) {
   if (d > 8192) return hipErrorInvalidValue;
   rmsnorm_kernel<<<T, 256, 0, st>>>(resid, part, nparts, T, gain, outP, d, eps);
   return hipGetLastError();
 }
-hipError_t hat_launch_rope_append(const HatPlanDev& p, bf16_t* qkv, const float2* table, bf16_t* pool_layer, int H,
+hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, bf16_t* pool_layer, int H,
                                   int hd, hipStream_t st) {
   const size_t n = (size_t)p.T * H * (hd >> 4);
   rope_append_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, H, hd);
   return hipGetLastError();
 }
-hipError_t hat_launch_retile(bf16_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1, const bf16_t* src2,
+hipError_t hat_launch_retile(act_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1, const bf16_t* src2,
                              int n0, int Ks, int mode, hipStream_t st) {
   const size_t n = (size_t)Nw * (Kd >> 3);
   retile_kernel<<<blocks_for(n, 256), 256, 0, st>>>(dst, Nw, Kd, src0, src1, src2, n0, Ks, mode);
@@ -328,7 +338,7 @@ hipError_t hat_launch_kv_export(const bf16_t* pool_layer, const int32_t* pages, 
   kv_export_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, pages, pos0, n, k, v, H, hd);
   return hipGetLastError();
 }
-hipError_t hat_launch_unpack_p32(const bf16_t* srcP, int row_len, int col0, int ncols, int T, float* dst,
+hipError_t hat_launch_unpack_p32(const act_t* srcP, int row_len, int col0, int ncols, int T, float* dst,
                                  hipStream_t st) {
   unpack_p32_kernel<<<blocks_for((size_t)T * ncols, 256), 256, 0, st>>>(srcP, row_len, col0, ncols, T, dst);
   return hipGetLastError();

@@ -1,11 +1,11 @@
-// bf16 MFMA GEMM for the projection and feed-forward matrices of a decoder layer
+// fp16 MFMA GEMM for the projection and feed-forward matrices of a decoder layer
 // (paper Sec. 2.1: self-attention module + feed-forward network; these four
 // products are the bulk of a chunk step's arithmetic).
 //
 //   out[t, f] = sum_k X[t, k] * W[f, k]      X: activations, W: weights [out, in]
 //
 // Both operands are in the P32 layout (hat_layout.h).  The kernel computes the
-// transposed product C^T = W * X^T with v_mfma_f32_32x32x16_bf16: MFMA rows are
+// transposed product C^T = W * X^T with v_mfma_f32_32x32x16_f16: MFMA rows are
 // output features, MFMA columns are tokens.  In the accumulator a lane then owns
 // one token and runs of 4 consecutive features, which is exactly an 8-byte piece
 // of the P32 layout of the *next* operand, so every epilogue stores coalesced.
@@ -30,14 +30,16 @@
 #include "hat_kernels.h"
 #include "hat_layout.h"
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
+// fp32 -> fp16, round to nearest even, saturating instead of overflowing to infinity
+__device__ __forceinline__ _Float16 to_act(float x) { return (_Float16)__builtin_amdgcn_fmed3f(x, -65504.f, 65504.f); }
 
 // compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
 template <class F, int... I>
@@ -50,9 +52,9 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 template <int OFF>
-__device__ __forceinline__ bf16x8 lds_read(uint32_t addr) {
+__device__ __forceinline__ f16x8 lds_read(uint32_t addr) {
   static_assert(OFF >= 0 && OFF < 65536, "ds_read offset field is 16 bits");
-  bf16x8 v;
+  f16x8 v;
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
   return v;
 }
@@ -64,7 +66,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // threaded through empty asm statements (volatile asm keeps its order) so that no
 // MFMA using them can be scheduled above the wait.
 template <int N>
-__device__ __forceinline__ void wait_operands(bf16x8 (&v)[N]) {
+__device__ __forceinline__ void wait_operands(f16x8 (&v)[N]) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]));
 #pragma unroll
   for (int i = 1; i < N; ++i) asm volatile("" : "+v"(v[i]));
@@ -122,13 +124,13 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   const int nkt = kt1 - kt0;
 
   // per-wave chunk sources (per-lane address); destinations are wave-uniform
-  const bf16_t* src[LPW];
+  const act_t* src[LPW];
   const size_t krow = (size_t)(g.K >> 3) * 256;  // elements per panel
 #pragma unroll
   for (int c = 0; c < LPW; ++c) {
     const int ch = wave * LPW + c;
     const int q = ch / CPS, sub = ch % CPS;
-    const bf16_t* base;
+    const act_t* base;
     if (q < PF) {
       base = g.W + (size_t)(ft * PF + q) * krow;
     } else {
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
 
     const uint32_t sbase = lds_base + (i % NSTAGE) * STAGE;
     const uint32_t aW = sbase + offW, aX = sbase + offX;
-    bf16x8 a[2][MI], bb[2][NJ];
+    f16x8 a[2][MI], bb[2][NJ];
     static_for<MI>([&](auto ii) { a[0][ii] = lds_read<ii * SLAB>(aW); });
     static_for<NJ>([&](auto jj) { bb[0][jj] = lds_read<jj * SLAB>(aX); });
     static_for<KS>([&](auto ks) {
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
       for (int ii = 0; ii < MI; ++ii)
 #pragma unroll
         for (int jj = 0; jj < NJ; ++jj)
-          acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][ii], bb[cur][jj], acc[ii][jj], 0, 0, 0);
+          acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][ii], bb[cur][jj], acc[ii][jj], 0, 0, 0);
     });
   }
 
@@ -214,10 +216,10 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int f = fb + 8 * q + 4 * h;
-          bf16x4 v;
+          f16x4 v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = (__bf16)acc[i][j][4 * q + e];
-          *(bf16x4*)(g.outP + p32_index(tok, f, g.Nout)) = v;
+          for (int e = 0; e < 4; ++e) v[e] = to_act(acc[i][j][4 * q + e]);
+          *(f16x4*)(g.outP + p32_index(tok, f, g.Nout)) = v;
         }
       }
     } else if constexpr (EPI == HAT_EPI_SWIGLU) {
@@ -229,10 +231,10 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int f = fb + 8 * q + 4 * h;
-            bf16x4 v;
+            f16x4 v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = (__bf16)(silu_f(acc[i][j][4 * q + e]) * acc[i + 1][j][4 * q + e]);
-            *(bf16x4*)(g.outP + p32_index(tok, f, g.Nout)) = v;
+            for (int e = 0; e < 4; ++e) v[e] = to_act(silu_f(acc[i][j][4 * q + e]) * acc[i + 1][j][4 * q + e]);
+            *(f16x4*)(g.outP + p32_index(tok, f, g.Nout)) = v;
           }
         }
       }

@@ -5,7 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-typedef __bf16 bf16_t;
+typedef __bf16 bf16_t;    // storage type of the callers' weights, of hidden in/out and of the KV cache
+typedef _Float16 act_t;   // arithmetic type of the MFMA operands: re-tiled weights and all activations
 
 constexpr int HAT_MAX_VERIFY_ROWS = 8;  // query rows of a verify work item
 
@@ -17,13 +18,13 @@ enum HatEpilogue {
 };
 
 struct HatGemm {
-  const bf16_t* W;  // P32 [Nw, K], Nw multiple of 256, padding rows zero
-  const bf16_t* X;  // P32 [>= roundup(T,32), K]
+  const act_t* W;   // P32 [Nw, K], Nw multiple of 256, padding rows zero
+  const act_t* X;   // P32 [>= roundup(T,32), K]
   int K;            // multiple of 64
   int T;            // valid rows of X
   int Nw;           // rows of W including padding
   int Nout;         // logical output features (EPI_SWIGLU: Nw/2 >= Nout)
-  bf16_t* outP;     // EPI_P32 / EPI_SWIGLU
+  act_t* outP;      // EPI_P32 / EPI_SWIGLU
   float* resid;     // EPI_RESID, K not split: resid[t, f] += result
   float* part;      // EPI_RESID, K split s ways: part[z][t][f] = partial sum of split z (may be null: no split)
   int part_rows;    // capacity of `part` in rows of Nout floats (bounds ksplit * T)
@@ -40,11 +41,11 @@ hipError_t hat_launch_gemm(const HatGemm& g, const HatGemmPlan& p, hipStream_t s
 hipError_t hat_gemm_init();  // one-time function attributes (dynamic LDS size)
 
 // ---- weight re-tiling (create time) -----------------------------------------
-// dst: P32 [Nw, Kd].  mode 0: row R <- src0[R] (R < n0), else 0.
+// dst: P32 [Nw, Kd] in act_t (bf16 -> fp16 is exact for |w| in [2^-17, 65504]).  mode 0: row R <- src0[R] (R < n0), else 0.
 // mode 1 (qkv): rows [0,n0) <- src0, [n0,2n0) <- src1, [2n0,3n0) <- src2.
 // mode 2 (gate/up): row R: blk=R/64, w=R%64; f = 32*blk + w%32; (w<32 ? src0 : src1)[f], zero if f >= n0.
 // Source rows have Ks elements (Ks <= Kd; columns beyond Ks are zero).
-hipError_t hat_launch_retile(bf16_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1,
+hipError_t hat_launch_retile(act_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1,
                              const bf16_t* src2, int n0, int Ks, int mode, hipStream_t st);
 hipError_t hat_launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStream_t st);
 
@@ -68,10 +69,10 @@ hipError_t hat_launch_scatter(const HatPlanDev& p, const float* resid, const flo
 hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, float2* table, int half, hipStream_t st);
 // x = resid + sum of nparts partial sums (part[i][t][:], stride T*d); if nparts > 0 the sum is
 // written back to resid.  out = rmsnorm(x) * gain as bf16 in P32 layout.
-hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, bf16_t* outP, int T,
+hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, act_t* outP, int T,
                               int d, float eps, hipStream_t st);
 // qkv: P32 [., 3d]; rotates q in place, writes rotated k and v into the pool of one layer
-hipError_t hat_launch_rope_append(const HatPlanDev& p, bf16_t* qkv, const float2* table, bf16_t* pool_layer,
+hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, bf16_t* pool_layer,
                                   int H, int hd, hipStream_t st);
 
 // ---- attention ---------------------------------------------------------------
@@ -86,15 +87,17 @@ struct HatAttnItem {
   int32_t pad0, pad1;
 };
 struct HatMergeItem {
-  int32_t row0;      // first batch row
-  int32_t nrows;
-  int32_t part_row;  // partial rows of split i start at part_row + i*nrows
+  int32_t row0;      // first batch row of this group
+  int32_t nrows;     // rows in the group (<= 16)
+  int32_t part_row;  // partial row of split 0 for row0; split i is at part_row + i*stride
   int32_t nsplit;
+  int32_t stride;    // partial rows between consecutive splits (= rows of the attention item)
+  int32_t pad0, pad1, pad2;
 };
 struct HatAttn {
-  const bf16_t* qkv;         // P32 [., 3d]; q = columns [0, d)
+  const act_t* qkv;          // P32 [., 3d]; q = columns [0, d)
   const bf16_t* pool_layer;  // this layer's pages
-  bf16_t* outP;              // P32 [., d]
+  act_t* outP;               // P32 [., d]
   float* part_o;             // [part rows][H][hd] unnormalised partial outputs
   float2* part_ml;           // [part rows][H] (running max in log2 units, sum)
   const HatAttnItem* items;
@@ -113,5 +116,5 @@ hipError_t hat_launch_kv_import(bf16_t* pool_layer, const int32_t* pages, int po
 hipError_t hat_launch_kv_export(const bf16_t* pool_layer, const int32_t* pages, int pos0, int n, bf16_t* k,
                                 bf16_t* v, int H, int hd, hipStream_t st);
 // P32 [., ncols_total] columns [col0, col0+ncols) -> fp32 row-major [T, ncols]
-hipError_t hat_launch_unpack_p32(const bf16_t* srcP, int row_len, int col0, int ncols, int T, float* dst,
+hipError_t hat_launch_unpack_p32(const act_t* srcP, int row_len, int col0, int ncols, int T, float* dst,
                                  hipStream_t st);

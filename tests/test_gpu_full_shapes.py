@@ -1,0 +1,225 @@
+"""GPU parity at the full widths of the benchmark configurations.
+
+The oracle cannot run whole 30/38-layer workloads in test time, so each case
+either (a) runs the oracle on a sample it can afford -- reduced depth at full
+width, or a subset of the devices of a step (segments never interact, so the
+oracle may follow any subset while the GPU processes the whole batch) -- or
+(b) checks a property that holds at any size (chunk-split invariance at full
+depth, integer page state against the page model at every step).
+Tolerance as elsewhere: max|gpu - ref| / max|ref| <= 2e-2 per segment."""
+import numpy as np
+import pytest
+
+import hat_inputs as hi
+from gpu_util import rel_err, rel_l2, to_dev_bf16, to_np, dev_weights
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def build(cfg, seed, n_pages, weights=None, **kw):
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2503_18989_amd import HatMid
+    if weights is None:
+        with ThreadPoolExecutor(max_workers=16) as ex:
+            weights = list(ex.map(lambda l: hi.layer_weights(cfg, l, seed), range(cfg["n_layers"])))
+    gpu = HatMid(cfg, [dev_weights(w) for w in weights], n_pages=n_pages, **kw)
+    return gpu, weights
+
+
+def device_random_kv(n, H, hd, seed):
+    import torch
+    g = torch.Generator(device="cuda"); g.manual_seed(seed)
+    k = (torch.randn((n, H, hd), generator=g, device="cuda") * 1.28).to(torch.bfloat16)
+    v = (torch.randn((n, H, hd), generator=g, device="cuda") * 1.28).to(torch.bfloat16)
+    return k, v
+
+
+def check(o, r, what=""):
+    assert np.all(np.isfinite(o)), what
+    e = rel_err(o, r)
+    assert e <= TOL, "%s rel err %.3e (l2 %.3e)" % (what, e, rel_l2(o, r))
+    return e
+
+
+def test_cfg2_7b_full_depth_first_chunk_and_split_invariance():
+    """30 layers, d 4096: the oracle follows the first 256-row chunk through all
+    30 layers; the whole 2048-row prompt is then checked GPU-vs-GPU between the
+    benchmark's 8x256 split and a 4x512 split (chunked prefill is a re-scheduling)."""
+    import torch
+    from oracle import OracleMiddle
+    from paper_2503_18989_amd import Segment
+    cfg = hi.MID7B
+    seed = 2000
+    gpu, weights = build(cfg, seed, n_pages=2 * 2048 // 16 + 8, max_devices=4, max_step_tokens=512, max_pos=2048)
+    xs = [hi.hidden_rows(256, cfg["d_model"], seed, i) for i in range(8)]
+    outs = []
+    for i, x in enumerate(xs):
+        outs.append(to_np(gpu.forward([Segment(0, hi.CHUNK, 256 * i, to_dev_bf16(x))])[0]))
+    torch.cuda.synchronize()
+    ref = OracleMiddle(cfg, lambda l: weights[l])
+    y0 = ref.forward([(0, 0, xs[0])])[0]
+    e = check(outs[0], y0, "chunk 0 through 30 layers")
+    print("cfg2 full depth: rel err %.3e, l2 %.3e" % (e, rel_l2(outs[0], y0)))
+    # K/V of the last layer for the first chunk
+    k, v = gpu.kv_export(0, cfg["n_layers"] - 1, 0, 256)
+    assert rel_err(to_np(k), ref.kv[0][-1][0]) < TOL and rel_err(to_np(v), ref.kv[0][-1][1]) < TOL
+    # a different split of the same prompt on a second device
+    xall = np.concatenate(xs)
+    outs2 = []
+    for i in range(4):
+        outs2.append(to_np(gpu.forward([Segment(1, hi.CHUNK, 512 * i, to_dev_bf16(xall[512 * i:512 * (i + 1)]))])[0]))
+    torch.cuda.synchronize()
+    a, b = np.concatenate(outs), np.concatenate(outs2)
+    assert rel_err(a, b) <= TOL / 2, "8x256 vs 4x512 differ by %.3e" % rel_err(a, b)
+    assert gpu.kv_query(0)[0] == 2048 and gpu.kv_query(1)[0] == 2048
+    gpu.close()
+
+
+def test_cfg2_7b_two_layers_all_chunks():
+    """Full width, 2 layers: all 8 chunks of the 2048-row prompt against the oracle."""
+    import torch
+    from oracle import OracleMiddle, PageModel
+    from paper_2503_18989_amd import Segment
+    cfg = hi.with_layers(hi.MID7B, 2)
+    seed = 2000
+    gpu, weights = build(cfg, seed, n_pages=2048 // 16 + 8, max_devices=2, max_step_tokens=256, max_pos=2048)
+    ref = OracleMiddle(cfg, weights)
+    pm = PageModel(2048 // 16 + 8, max_devices=2, max_step_tokens=256, max_pos=2048)
+    worst = 0.0
+    for i, step in enumerate(hi.single_prompt_schedule()):
+        dev, kind, start, n = step[0]
+        x = hi.hidden_rows(n, cfg["d_model"], seed, i)
+        y = to_np(gpu.forward([Segment(dev, kind, start, to_dev_bf16(x))])[0])
+        torch.cuda.synchronize()
+        worst = max(worst, check(y, ref.forward([(dev, start, x)])[0], "chunk %d" % i))
+        pm.step(step)
+        assert gpu.kv_query(0) == pm.query(0)
+    print("cfg2 2 layers: worst rel err %.3e" % worst)
+    gpu.close()
+
+
+def test_cfg3_7b_mixed_step_sampled_devices():
+    """30 devices, prefixes U[256,4096] installed by import, one mixed step (10 chunks from
+    {128,256,512} + 20 verify segments of 5 rows); the oracle follows 3 chunk devices and
+    4 verify devices, the page model all 30."""
+    import torch
+    from oracle import OracleMiddle, PageModel
+    from paper_2503_18989_amd import Segment
+    cfg = hi.with_layers(hi.MID7B, 2)
+    seed = 3000
+    H, hd, d = cfg["n_heads"], cfg["head_dim"], cfg["d_model"]
+    pref = hi.mixed_prefixes(seed)
+    segs = hi.mixed_step(seed, 0, pref)
+    T = sum(s[3] for s in segs)
+    n_pages = sum((p + s[3] + 15) // 16 for p, s in zip(pref, segs)) + 32
+    gpu, weights = build(cfg, seed, n_pages=n_pages, max_devices=30, max_step_tokens=T, max_pos=8192)
+    ref = OracleMiddle(cfg, weights)
+    pm = PageModel(n_pages, max_devices=30, max_step_tokens=8192, max_pos=8192)
+    chunk_devs = [s[0] for s in segs if s[1] == hi.CHUNK]
+    verify_devs = [s[0] for s in segs if s[1] == hi.VERIFY]
+    sampled = set(sorted(chunk_devs, key=lambda dv: segs[dv][3])[:2] + chunk_devs[-1:] + verify_devs[:4])
+    for dev in range(30):
+        pm.step([(dev, 0, 0, pref[dev])])
+        for l in range(cfg["n_layers"]):
+            if dev in sampled:
+                k, v = hi.kv_prefix(pref[dev], H, hd, seed, dev, l)
+                gpu.kv_import(dev, l, 0, to_dev_bf16(k).view(-1, H, hd), to_dev_bf16(v).view(-1, H, hd))
+                ref.import_kv(dev, l, 0, k, v)
+            else:
+                k, v = device_random_kv(pref[dev], H, hd, seed * 100 + dev * 4 + l)
+                gpu.kv_import(dev, l, 0, k, v)
+        assert gpu.kv_query(dev) == pm.query(dev)
+    xs = [hi.hidden_rows(s[3], d, seed, s[0]) for s in segs]
+    outs = gpu.forward([Segment(s[0], s[1], s[2], to_dev_bf16(x)) for s, x in zip(segs, xs)])
+    torch.cuda.synchronize()
+    pm.step(segs)
+    for dev in range(30):
+        assert gpu.kv_query(dev) == pm.query(dev)
+    refs = ref.forward([(s[0], s[2], x) for s, x in zip(segs, xs) if s[0] in sampled])
+    got = [to_np(o) for s, o in zip(segs, outs) if s[0] in sampled]
+    worst = max(check(o, r, "device") for o, r in zip(got, refs))
+    for o in outs:
+        assert torch.isfinite(o.float()).all()
+    print("cfg3: T=%d, sampled %d segments, worst rel err %.3e" % (T, len(refs), worst))
+    gpu.close()
+
+
+def test_cfg4_7b_verify_heavy_64_steps_with_rollback():
+    """30 devices x 5 draft rows per step, cache lengths U[1024,8192], 64 steps with the
+    seeded accept/rollback pattern.  Page ids, slots and lengths of all 30 devices are
+    compared with the page model after every step; the oracle follows 3 devices through
+    all 64 steps (outputs compared at every step, so drift after 63 rollbacks shows)."""
+    import torch
+    from oracle import OracleMiddle, PageModel
+    from paper_2503_18989_amd import Segment
+    cfg = hi.with_layers(hi.MID7B, 2)
+    seed = 4000
+    H, hd, d = cfg["n_heads"], cfg["head_dim"], cfg["d_model"]
+    lengths = hi.verify_lengths(seed)
+    sched = hi.verify_schedule(seed, lengths, steps=64)
+    n_pages = sum((ln + 64 * 5 + 15) // 16 for ln in lengths) + 32
+    gpu, weights = build(cfg, seed, n_pages=n_pages, max_devices=30, max_step_tokens=256, max_pos=8192 + 64 * 5 + 16)
+    ref = OracleMiddle(cfg, weights)
+    pm = PageModel(n_pages, max_devices=30, max_step_tokens=16384, max_pos=8192 + 64 * 5 + 16)
+    order = np.argsort(lengths)
+    sampled = {int(order[0]), int(order[15]), int(order[-1])}      # shortest, median, longest cache
+    for dev in range(30):
+        pm.step([(dev, 0, 0, lengths[dev])])
+        for l in range(cfg["n_layers"]):
+            if dev in sampled:
+                k, v = hi.kv_prefix(lengths[dev], H, hd, seed, dev, l)
+                gpu.kv_import(dev, l, 0, to_dev_bf16(k).view(-1, H, hd), to_dev_bf16(v).view(-1, H, hd))
+                ref.import_kv(dev, l, 0, k, v)
+            else:
+                k, v = device_random_kv(lengths[dev], H, hd, seed * 100 + dev * 4 + l)
+                gpu.kv_import(dev, l, 0, k, v)
+    worst = 0.0
+    for it, step in enumerate(sched):
+        xs = [hi.hidden_rows(5, d, seed, it, s[0]) for s in step]
+        outs = gpu.forward([Segment(s[0], s[1], s[2], to_dev_bf16(x)) for s, x in zip(step, xs)])
+        torch.cuda.synchronize()
+        pm.step(step)
+        for dev in range(30):
+            assert gpu.kv_query(dev) == pm.query(dev), "step %d device %d" % (it, dev)
+        refs = ref.forward([(s[0], s[2], x) for s, x in zip(step, xs) if s[0] in sampled])
+        got = [to_np(o) for s, o in zip(step, outs) if s[0] in sampled]
+        for o, r in zip(got, refs):
+            worst = max(worst, check(o, r, "step %d" % it))
+    print("cfg4: 64 steps, worst rel err %.3e" % worst)
+    gpu.close()
+
+
+@pytest.mark.parametrize("chunk", [64, 128, 256, 512, 1024])
+def test_cfg5_13b_last_chunk_of_each_size(chunk):
+    """13B width (d 5120, 40 heads, FFN 13824), 2 layers: 8 devices with 8192-row prompts,
+    the LAST chunk of each chunk size batched over the 8 devices (T = 8*chunk rows, prefix
+    8192-chunk installed by import); the oracle follows one device."""
+    import torch
+    from oracle import OracleMiddle
+    from paper_2503_18989_amd import Segment
+    cfg = hi.with_layers(hi.MID13B, 2)
+    seed = 5000
+    H, hd, d = cfg["n_heads"], cfg["head_dim"], cfg["d_model"]
+    start = 8192 - chunk
+    n_pages = 8 * (8192 // 16) + 16
+    gpu, weights = build(cfg, seed, n_pages=n_pages, max_devices=8, max_step_tokens=8 * chunk, max_pos=8192)
+    ref = OracleMiddle(cfg, weights)
+    for dev in range(8):
+        for l in range(2):
+            if dev == 3:
+                k, v = hi.kv_prefix(start, H, hd, seed, dev, l)
+                gpu.kv_import(dev, l, 0, to_dev_bf16(k).view(-1, H, hd), to_dev_bf16(v).view(-1, H, hd))
+                ref.import_kv(dev, l, 0, k, v)
+            else:
+                k, v = device_random_kv(start, H, hd, seed * 100 + dev * 4 + l)
+                gpu.kv_import(dev, l, 0, k, v)
+    xs = [hi.hidden_rows(chunk, d, seed, chunk, dev) for dev in range(8)]
+    outs = gpu.forward([Segment(dev, hi.CHUNK, start, to_dev_bf16(xs[dev])) for dev in range(8)])
+    torch.cuda.synchronize()
+    for dev in range(8):
+        assert gpu.kv_query(dev)[0] == 8192 and torch.isfinite(outs[dev].float()).all()
+    y = ref.forward([(3, start, xs[3])])[0]
+    e = check(to_np(outs[3]), y, "chunk %d" % chunk)
+    print("cfg5 chunk %d: rel err %.3e" % (chunk, e))
+    gpu.close()
