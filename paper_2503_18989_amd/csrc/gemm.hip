@@ -192,11 +192,15 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
         static_for<MI>([&](auto ii) { a[cur ^ 1][ii] = lds_read<ii * SLAB + (ks + 1) * 1024>(aW); });
         static_for<NJ>([&](auto jj) { bb[cur ^ 1][jj] = lds_read<jj * SLAB + (ks + 1) * 1024>(aX); });
       }
+      // keep the next k-step's operand reads ahead of this k-step's MFMAs (the scheduler
+      // would otherwise sink them behind the MFMAs and expose the LDS latency)
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ii = 0; ii < MI; ++ii)
 #pragma unroll
         for (int jj = 0; jj < NJ; ++jj)
           acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][ii], bb[cur][jj], acc[ii][jj], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     });
   }
 
