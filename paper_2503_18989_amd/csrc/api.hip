@@ -589,10 +589,10 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
     g.epilogue = HAT_EPI_P32;
     hat_status_t rc = run_gemm(HAT_K_GEMM_QKV, g, nullptr);
     if (rc != HAT_OK) return rc;
-    LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_append(pd, h->b.qkv, h->b.table, pool_l, s.H, s.hd, st));
+    LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_append(pd, h->b.qkv, h->b.table, pool_l, c.n_pages, s.H, s.hd, st));
     HatAttn a{};
     a.qkv = h->b.qkv; a.pool_layer = pool_l; a.outP = h->b.attn; a.part_o = h->b.part_o; a.part_ml = h->b.part_ml;
-    a.H = s.H; a.hd = s.hd; a.d = s.d;
+    a.H = s.H; a.hd = s.hd; a.d = s.d; a.n_pages = c.n_pages;
     if (!citems.empty()) {
       a.items = (const HatAttnItem*)(D + o_ci); a.n_items = (int)citems.size();
       LAUNCH(h, st, HAT_K_ATTN_CHUNK, hat_launch_attn_chunk(pd, a, st));
@@ -689,7 +689,7 @@ hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, i
   hipStream_t st = (hipStream_t)hip_stream;
   hat_status_t rc = fixture_pages(h, d, pos0, n, st);
   if (rc != HAT_OK) return rc;
-  HIP_TRY(h, hat_launch_kv_import(h->pool + (size_t)layer * h->layer_pool_elems, h->b.fixture_pages, pos0, n,
+  HIP_TRY(h, hat_launch_kv_import(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages, pos0, n,
                                   (const bf16_t*)k, (const bf16_t*)v, c.n_heads, c.head_dim, st));
   return HAT_OK;
 }
@@ -705,7 +705,7 @@ hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, i
   hipStream_t st = (hipStream_t)hip_stream;
   hat_status_t rc = fixture_pages(h, d, pos0, n, st);
   if (rc != HAT_OK) return rc;
-  HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, h->b.fixture_pages, pos0, n,
+  HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages, pos0, n,
                                   (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, st));
   return HAT_OK;
 }

@@ -121,7 +121,7 @@ __device__ __forceinline__ _Float16 to_act(float x) { return (_Float16)__builtin
 
 // ------------------------------------------------------------------ verify
 template <int HD>
-__global__ __launch_bounds__(256) void attn_verify_kernel(HatPlanDev p, HatAttn a) {
+__global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAttn a) {
   constexpr int NS = HD / 16;  // k-steps of Q K^T
   constexpr int NC = HD / 32;  // 32-row blocks of O^T
   constexpr int REC = 2 * 16 * HD;  // elements of one (page, head) record
@@ -152,37 +152,41 @@ __global__ __launch_bounds__(256) void attn_verify_kernel(HatPlanDev p, HatAttn 
 
   int kv_end = it.kv_end < sg.kv_len ? it.kv_end : sg.kv_len;
   const int pair0 = it.kv_begin >> 5, pair1 = (kv_end + 31) >> 5;
-  const bf16_t* pool = a.pool_layer + (size_t)head * REC;
-  const size_t page_stride = (size_t)a.H * REC;
+  const bf16_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
+  const size_t page_stride = REC;
 
-  for (int pp = pair0 + wave; pp < pair1; pp += 4) {
-    const int key0 = pp << 5;
+  // Two register stages of raw page data: the loads of this wave's next page pair are in
+  // flight while the current pair is widened, multiplied and soft-maxed.
+  u32x4 kraw[1][NS], varaw[1][NC], vbraw[1][NC];
+  auto load_pair = [&](int pp, int st) {
     int ia = 2 * pp, ib = 2 * pp + 1;
     ib = ib < sg.npages ? ib : sg.npages - 1;
     const bf16_t* recA = pool + (size_t)sg.pt[ia] * page_stride;
     const bf16_t* recB = pool + (size_t)sg.pt[ib] * page_stride;
     const bf16_t* krec = (n < 16) ? recA : recB;
-    u32x4 kraw[NS], varaw[NC], vbraw[NC];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) kraw[s] = *(const u32x4*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8);
+    for (int s = 0; s < NS; ++s) kraw[st][s] = *(const u32x4*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8);
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      varaw[c] = *(const u32x4*)(recA + 16 * HD + c * 512 + lane * 8);
-      vbraw[c] = *(const u32x4*)(recB + 16 * HD + c * 512 + lane * 8);
+      varaw[st][c] = *(const u32x4*)(recA + 16 * HD + c * 512 + lane * 8);
+      vbraw[st][c] = *(const u32x4*)(recB + 16 * HD + c * 512 + lane * 8);
     }
+  };
+  auto compute_pair = [&](int pp, int st) {
+    const int key0 = pp << 5;
     f16x8 kreg[NS], va[NC], vb[NC];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) kreg[s] = kv_to_f16(kraw[s]);
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      va[c] = kv_to_f16(varaw[c]);
-      vb[c] = kv_to_f16(vbraw[c]);
-    }
+    for (int s = 0; s < NS; ++s) kreg[s] = kv_to_f16(kraw[st][s]);
     f32x16 sacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
     for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[s], qreg[s], sacc, 0, 0, 0);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      va[c] = kv_to_f16(varaw[st][c]);
+      vb[c] = kv_to_f16(vbraw[st][c]);
+    }
     if (key0 + 32 > sg.kv_len) {
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
@@ -197,6 +201,12 @@ __global__ __launch_bounds__(256) void attn_verify_kernel(HatPlanDev p, HatAttn 
       o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[c], p0, o[c], 0, 0, 0);
       o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb[c], p1, o[c], 0, 0, 0);
     }
+  };
+  // one register stage per wave; two workgroups share a CU (<= 256 VGPRs), so one wave's
+  // loads are in flight while the other wave on the SIMD computes
+  for (int pp = pair0 + wave; pp < pair1; pp += 4) {
+    load_pair(pp, 0);
+    compute_pair(pp, 0);
   }
   l_run += __shfl_xor(l_run, 32);
 
@@ -283,8 +293,8 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a
   const int need = sg.start + it.q0 + it.nq;
   kv_end = kv_end < need ? kv_end : need;
   const int st0 = it.kv_begin >> 6, st1 = (kv_end + 63) >> 6;
-  const bf16_t* pool = a.pool_layer + (size_t)head * REC;
-  const size_t page_stride = (size_t)a.H * REC;
+  const bf16_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
+  const size_t page_stride = REC;
 
   u32x4 regs[LPT];
   auto gload = [&](int st) {

@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ resid,
 // halves of 8 rotation pairs.  q is rotated in place (fp16); rotated k and v are
 // rounded to bf16 and go to the row's (page, slot) of this layer's pool.
 __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const float2* __restrict__ table,
-                                   bf16_t* __restrict__ pool, int H, int hd) {
+                                   bf16_t* __restrict__ pool, int n_pages, int H, int hd) {
   const int half_oct = hd >> 4;                 // octets per half head
   const int per_row = H * half_oct;
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
@@ -172,7 +172,7 @@ __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const 
 
   const int dst = p.kv_dst[t];
   const int page = dst >> 4, slot = dst & 15;
-  bf16_t* kt = pool + ((size_t)page * H + hh) * kv_head_elems(hd);
+  bf16_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
   bf16_t* vt = kt + 16 * hd;
   *(bf16x8*)(kt + ktile_index(slot, o * 8)) = rkl;
   *(bf16x8*)(kt + ktile_index(slot, o * 8 + (hd >> 1))) = rkh;
@@ -239,7 +239,7 @@ __global__ void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __rest
 
 // ---------------------------------------------------------------- fixtures
 // one thread per (row, head, octet)
-__global__ void kv_import_kernel(bf16_t* __restrict__ pool, const int32_t* __restrict__ pages, int pos0, int n,
+__global__ void kv_import_kernel(bf16_t* __restrict__ pool, int n_pages, const int32_t* __restrict__ pages, int pos0, int n,
                                  const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int H, int hd) {
   const int octs = hd >> 3;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -249,7 +249,7 @@ __global__ void kv_import_kernel(bf16_t* __restrict__ pool, const int32_t* __res
   const int r = (int)(idx / ((size_t)octs * H));
   const int pos = pos0 + r;
   const int page = pages[(pos >> 4) - (pos0 >> 4)], slot = pos & 15;
-  bf16_t* kt = pool + ((size_t)page * H + hh) * kv_head_elems(hd);
+  bf16_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
   bf16_t* vt = kt + 16 * hd;
   const size_t so = ((size_t)r * H + hh) * hd + o * 8;
   *(bf16x8*)(kt + ktile_index(slot, o * 8)) = *(const bf16x8*)(k + so);
@@ -258,7 +258,7 @@ __global__ void kv_import_kernel(bf16_t* __restrict__ pool, const int32_t* __res
   for (int e = 0; e < 8; ++e) vt[vtile_index(slot, o * 8 + e)] = vv[e];
 }
 
-__global__ void kv_export_kernel(const bf16_t* __restrict__ pool, const int32_t* __restrict__ pages, int pos0, int n,
+__global__ void kv_export_kernel(const bf16_t* __restrict__ pool, int n_pages, const int32_t* __restrict__ pages, int pos0, int n,
                                  bf16_t* __restrict__ k, bf16_t* __restrict__ v, int H, int hd) {
   const int octs = hd >> 3;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -268,7 +268,7 @@ __global__ void kv_export_kernel(const bf16_t* __restrict__ pool, const int32_t*
   const int r = (int)(idx / ((size_t)octs * H));
   const int pos = pos0 + r;
   const int page = pages[(pos >> 4) - (pos0 >> 4)], slot = pos & 15;
-  const bf16_t* kt = pool + ((size_t)page * H + hh) * kv_head_elems(hd);
+  const bf16_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
   const bf16_t* vt = kt + 16 * hd;
   const size_t so = ((size_t)r * H + hh) * hd + o * 8;
   *(bf16x8*)(k + so) = *(const bf16x8*)(kt + ktile_index(slot, o * 8));
@@ -310,10 +310,10 @@ hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const
   rmsnorm_kernel<<<T, 256, 0, st>>>(resid, part, nparts, T, gain, outP, d, eps);
   return hipGetLastError();
 }
-hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, bf16_t* pool_layer, int H,
-                                  int hd, hipStream_t st) {
+hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, bf16_t* pool_layer,
+                                  int n_pages, int H, int hd, hipStream_t st) {
   const size_t n = (size_t)p.T * H * (hd >> 4);
-  rope_append_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, H, hd);
+  rope_append_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, hd);
   return hipGetLastError();
 }
 hipError_t hat_launch_retile(act_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1, const bf16_t* src2,
@@ -326,16 +326,16 @@ hipError_t hat_launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStrea
   bf16_to_f32_kernel<<<blocks_for(n, 256), 256, 0, st>>>(src, dst, n);
   return hipGetLastError();
 }
-hipError_t hat_launch_kv_import(bf16_t* pool_layer, const int32_t* pages, int pos0, int n, const bf16_t* k,
-                                const bf16_t* v, int H, int hd, hipStream_t st) {
+hipError_t hat_launch_kv_import(bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
+                                const bf16_t* k, const bf16_t* v, int H, int hd, hipStream_t st) {
   const size_t cnt = (size_t)n * H * (hd >> 3);
-  kv_import_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, pages, pos0, n, k, v, H, hd);
+  kv_import_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
   return hipGetLastError();
 }
-hipError_t hat_launch_kv_export(const bf16_t* pool_layer, const int32_t* pages, int pos0, int n, bf16_t* k, bf16_t* v,
-                                int H, int hd, hipStream_t st) {
+hipError_t hat_launch_kv_export(const bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
+                                bf16_t* k, bf16_t* v, int H, int hd, hipStream_t st) {
   const size_t cnt = (size_t)n * H * (hd >> 3);
-  kv_export_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, pages, pos0, n, k, v, H, hd);
+  kv_export_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
   return hipGetLastError();
 }
 hipError_t hat_launch_unpack_p32(const act_t* srcP, int row_len, int col0, int ncols, int T, float* dst,

@@ -73,7 +73,7 @@ hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const
                               int d, float eps, hipStream_t st);
 // qkv: P32 [., 3d]; rotates q in place, writes rotated k and v into the pool of one layer
 hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, bf16_t* pool_layer,
-                                  int H, int hd, hipStream_t st);
+                                  int n_pages, int H, int hd, hipStream_t st);
 
 // ---- attention ---------------------------------------------------------------
 // One work item = 32*QB query rows of one segment against keys [kv_begin, kv_end).
@@ -103,6 +103,7 @@ struct HatAttn {
   const HatAttnItem* items;
   int n_items;
   int H, hd, d;
+  int n_pages;               // pool capacity (pages per head and layer)
 };
 hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStream_t st);
 hipError_t hat_launch_attn_verify(const HatPlanDev& p, const HatAttn& a, hipStream_t st);
@@ -111,10 +112,10 @@ hipError_t hat_attn_init();
 
 // ---- fixtures ------------------------------------------------------------------
 // k, v: [n, H, hd] bf16 plain; pages: device array of the page ids covering the rows
-hipError_t hat_launch_kv_import(bf16_t* pool_layer, const int32_t* pages, int pos0, int n, const bf16_t* k,
-                                const bf16_t* v, int H, int hd, hipStream_t st);
-hipError_t hat_launch_kv_export(const bf16_t* pool_layer, const int32_t* pages, int pos0, int n, bf16_t* k,
-                                bf16_t* v, int H, int hd, hipStream_t st);
+hipError_t hat_launch_kv_import(bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
+                                const bf16_t* k, const bf16_t* v, int H, int hd, hipStream_t st);
+hipError_t hat_launch_kv_export(const bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
+                                bf16_t* k, bf16_t* v, int H, int hd, hipStream_t st);
 // P32 [., ncols_total] columns [col0, col0+ncols) -> fp32 row-major [T, ncols]
 hipError_t hat_launch_unpack_p32(const act_t* srcP, int row_len, int col0, int ncols, int T, float* dst,
                                  hipStream_t st);

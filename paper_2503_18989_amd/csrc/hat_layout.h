@@ -10,8 +10,9 @@
 //       element (r, k) of an [R, K] matrix, K % 8 == 0:
 //         ((r/32) * (K/8) + k/8) * 256 + (r%32) * 8 + k%8
 //
-// (2) KV pool.  pool[layer][page][head] = one K tile followed by one V tile, each
-//     16 tokens x head_dim bf16.
+// (2) KV pool.  pool[layer][head][page] = one K tile followed by one V tile, each
+//     16 tokens x head_dim bf16 (a device's consecutively allocated pages are one
+//     contiguous run per head).
 //       K tile: [hd/8][slot][8]                   (an octet-major 16-row panel)
 //       V tile: [hd/32][h][hd%32][j], where slot = 8*(j/4) + 4*h + j%4
 //     The V order is the order in which a lane of the S^T = K Q^T accumulator
