@@ -32,7 +32,8 @@ struct Shapes {
   int L, d, H, hd, F, Fpad;
   int Nqkv, No, Ngu, Nd;  // padded weight rows
   int Tcap;               // row capacity of activation buffers (multiple of 256)
-  int attn_target;        // workgroups an attention launch should reach
+  int attn_target;        // workgroups a chunk-attention launch should reach
+  int verify_target;      // workgroups a verify-attention launch should reach
   int chunk_items_cap, verify_items_cap, merge_cap;
   int part_rows_cap;
   int gemm_part_rows;     // rows of the split-K partial-sum buffer
@@ -61,15 +62,17 @@ Shapes make_shapes(const hat_mid_config_t& c) {
   s.Nd = round_up(s.d, 256);
   s.Tcap = round_up(c.max_step_tokens, 256);
   s.attn_target = 1024;
-  if (const char* e = getenv("HAT_ATTN_TARGET")) s.attn_target = std::max(1, atoi(e));
-  const int per_head = (s.attn_target + s.H - 1) / s.H;
+  s.verify_target = 2048;
+  if (const char* e = getenv("HAT_ATTN_TARGET")) s.attn_target = s.verify_target = std::max(1, atoi(e));
+  if (const char* e = getenv("HAT_VERIFY_TARGET")) s.verify_target = std::max(1, atoi(e));
+  const int per_head = (std::max(s.attn_target, s.verify_target) + s.H - 1) / s.H;
   s.chunk_items_cap = 2 * per_head + s.Tcap / 128 + c.max_devices + 2;
   s.verify_items_cap = 2 * per_head + c.max_devices + 2;
   s.merge_cap = s.Tcap / 16 + s.Tcap / 128 + 2 * c.max_devices + 2;
   s.part_rows_cap = 128 * (2 * per_head + 2) + HAT_MAX_VERIFY * s.verify_items_cap;
   s.gemm_part_rows = 4096;
   s.plan_words = (size_t)3 * s.Tcap + 8 * (size_t)c.max_devices + 16 + (size_t)c.n_pages + c.max_devices +
-                 8 * ((size_t)s.chunk_items_cap + s.verify_items_cap) + 8 * (size_t)s.merge_cap + 64;
+                 12 * ((size_t)s.chunk_items_cap + s.verify_items_cap) + 8 * (size_t)s.merge_cap + 64;
   return s;
 }
 
@@ -468,7 +471,7 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
 
   // ---- attention work lists
   {
-    const int per_head = (s.attn_target + s.H - 1) / s.H;  // items wanted
+    const int per_head = (s.verify_target + s.H - 1) / s.H;  // verify items wanted
     int part_row = 0;
     // rows of a split item are merged in groups of 16 (one workgroup per group and head)
     auto push_merge = [&](int row0, int nrows, int prow, int nsplit) {
@@ -498,6 +501,7 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
         for (int k = 0; k < ns; ++k) {
           HatAttnItem it{};
           it.seg = i; it.q0 = 0; it.nq = segs[i].n;
+          it.start = segs[i].start_pos; it.tok0 = P[o_toff + i]; it.kv_len = len; it.pt_off = P[o_spt + i];
           it.kv_begin = k * step; it.kv_end = std::min(len, (k + 1) * step);
           it.part_row = ns > 1 ? part_row + k * segs[i].n : -1;
           vitems.push_back(it);
@@ -528,6 +532,8 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
           for (int k = 0; k < ns; ++k) {
             HatAttnItem it{};
             it.seg = i; it.q0 = q0; it.nq = nq;
+            it.start = segs[i].start_pos; it.tok0 = P[o_toff + i]; it.kv_len = segs[i].start_pos + segs[i].n;
+            it.pt_off = P[o_spt + i];
             it.kv_begin = k * step; it.kv_end = std::min(need, (k + 1) * step);
             it.part_row = ns > 1 ? part_row + k * nq : -1;
             citems.push_back(it);
@@ -545,9 +551,9 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
     std::stable_sort(citems.begin(), citems.end(), by_cost);
     std::stable_sort(vitems.begin(), vitems.end(), by_cost);
   }
-  const size_t o_ci = take(8 * citems.size(), 8), o_vi = take(8 * vitems.size(), 8), o_mi = take(8 * mitems.size(), 8);
+  const size_t o_ci = take(12 * citems.size(), 4), o_vi = take(12 * vitems.size(), 4), o_mi = take(8 * mitems.size(), 8);
   if (w > s.plan_words) return fail(h, HAT_EINVAL, "internal: plan of %zu words exceeds capacity %zu", w, s.plan_words);
-  static_assert(sizeof(HatAttnItem) == 32 && sizeof(HatMergeItem) == 32, "plan item sizes");
+  static_assert(sizeof(HatAttnItem) == 48 && sizeof(HatMergeItem) == 32, "plan item sizes");
   if (!citems.empty()) memcpy(&P[o_ci], citems.data(), citems.size() * sizeof(HatAttnItem));
   if (!vitems.empty()) memcpy(&P[o_vi], vitems.data(), vitems.size() * sizeof(HatAttnItem));
   if (!mitems.empty()) memcpy(&P[o_mi], mitems.data(), mitems.size() * sizeof(HatMergeItem));

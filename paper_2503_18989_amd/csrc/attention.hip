@@ -43,14 +43,14 @@ struct SegInfo {
   const int32_t* pt;
 };
 
-__device__ __forceinline__ SegInfo seg_info(const HatPlanDev& p, int seg) {
+__device__ __forceinline__ SegInfo seg_info(const HatPlanDev& p, const HatAttnItem& it) {
   SegInfo s;
-  s.start = p.seg_start[seg];
-  s.tok0 = p.tok_off[seg];
-  s.nseg = p.tok_off[seg + 1] - s.tok0;
-  s.kv_len = s.start + s.nseg;
+  s.start = it.start;
+  s.tok0 = it.tok0;
+  s.kv_len = it.kv_len;
+  s.nseg = s.kv_len - s.start;
   s.npages = (s.kv_len + 15) >> 4;
-  s.pt = p.page_tbl + p.seg_pt[seg];
+  s.pt = p.page_tbl + it.pt_off;
   return s;
 }
 
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
 
   const HatAttnItem it = a.items[blockIdx.x];
   const int head = blockIdx.y;
-  const SegInfo sg = seg_info(p, it.seg);
+  const SegInfo sg = seg_info(p, it);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int half = lane >> 5, n = lane & 31;
   const int qi = n < it.nq ? n : it.nq - 1;  // clamp idle columns onto a real row
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a
 
   const HatAttnItem it = a.items[blockIdx.x];
   const int head = blockIdx.y;
-  const SegInfo sg = seg_info(p, it.seg);
+  const SegInfo sg = seg_info(p, it);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int half = lane >> 5, n = lane & 31;
   const int wq0 = it.q0 + 32 * wave;  // first row of this wave, relative to the segment

@@ -81,9 +81,15 @@ struct HatAttnItem {
   int32_t seg;       // segment index
   int32_t q0;        // first query row, relative to the segment
   int32_t nq;        // valid query rows in this item
-  int32_t kv_begin;  // multiple of 32
+  int32_t kv_begin;  // multiple of 64
   int32_t kv_end;    // exclusive; keys beyond the causal limit are masked
   int32_t part_row;  // >= 0: first row of this item's partial result; -1: write the final output
+  // copies of the segment's plan entries, so that a workgroup reaches its first page id
+  // after one dependent load instead of three
+  int32_t start;     // absolute position of the segment's first row
+  int32_t tok0;      // batch row of the segment's first row
+  int32_t kv_len;    // cache length after this step's append
+  int32_t pt_off;    // offset of the segment's page list in page_tbl
   int32_t pad0, pad1;
 };
 struct HatMergeItem {
