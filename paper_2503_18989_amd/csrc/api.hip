@@ -61,7 +61,7 @@ Shapes make_shapes(const hat_mid_config_t& c) {
   s.Ngu = round_up(2 * s.Fpad, 256);
   s.Nd = round_up(s.d, 256);
   s.Tcap = round_up(c.max_step_tokens, 256);
-  s.attn_target = 1024;
+  s.attn_target = 512;
   s.verify_target = 2048;
   if (const char* e = getenv("HAT_ATTN_TARGET")) s.attn_target = s.verify_target = std::max(1, atoi(e));
   if (const char* e = getenv("HAT_VERIFY_TARGET")) s.verify_target = std::max(1, atoi(e));
@@ -71,7 +71,7 @@ Shapes make_shapes(const hat_mid_config_t& c) {
   s.merge_cap = s.Tcap / 16 + s.Tcap / 128 + 2 * c.max_devices + 2;
   s.part_rows_cap = 128 * (2 * per_head + 2) + HAT_MAX_VERIFY * s.verify_items_cap;
   s.gemm_part_rows = 4096;
-  s.plan_words = (size_t)3 * s.Tcap + 8 * (size_t)c.max_devices + 16 + (size_t)c.n_pages + c.max_devices +
+  s.plan_words = (size_t)3 * s.Tcap + 8 * ((size_t)s.Tcap / 16 + 2 * (size_t)c.max_devices + 2) + 8 * (size_t)c.max_devices + 16 + (size_t)c.n_pages + c.max_devices +
                  12 * ((size_t)s.chunk_items_cap + s.verify_items_cap) + 8 * (size_t)s.merge_cap + 64;
   return s;
 }
@@ -442,6 +442,9 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
   const size_t o_toff = take(S + 1, 1), o_sstart = take(S, 1), o_spt = take(S, 1);
   const size_t o_in = take(2 * (size_t)S, 2), o_out = take(2 * (size_t)S, 2);
   const size_t o_pt = take(np_total, 1);
+  int n_append = 0;
+  for (int i = 0; i < S; ++i) n_append += ((segs[i].start_pos + segs[i].n - 1) >> 4) - (segs[i].start_pos >> 4) + 1;
+  const size_t o_app = take(8 * (size_t)n_append, 4);
 
   std::vector<HatAttnItem> citems, vitems;
   std::vector<HatMergeItem> mitems;
@@ -467,6 +470,17 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
       pt += (int)d.pages.size();
     }
     P[o_toff + S] = T;
+    HatAppendItem* ap = (HatAppendItem*)&P[o_app];
+    for (int i = 0; i < S; ++i) {
+      const hat_mid_segment_t& g = segs[i];
+      const DeviceState& d = h->dev[g.device_id];
+      for (int pg = g.start_pos >> 4; pg <= (g.start_pos + g.n - 1) >> 4; ++pg) {
+        HatAppendItem a{};
+        a.page = d.pages[pg]; a.pos0 = pg * 16; a.row0 = P[o_toff + i] + (a.pos0 - g.start_pos);
+        a.lo = std::max(g.start_pos, a.pos0); a.hi = std::min(g.start_pos + g.n, a.pos0 + 16);
+        *ap++ = a;
+      }
+    }
   }
 
   // ---- attention work lists
@@ -570,6 +584,7 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
   pd.pos = D + o_pos; pd.kv_dst = D + o_dst; pd.tok_seg = D + o_tseg; pd.tok_off = D + o_toff;
   pd.seg_start = D + o_sstart; pd.seg_pt = D + o_spt; pd.page_tbl = D + o_pt;
   pd.in_ptr = (const uint64_t*)(D + o_in); pd.out_ptr = (const uint64_t*)(D + o_out);
+  pd.append = (const HatAppendItem*)(D + o_app); pd.n_append = n_append;
 
   LAUNCH(h, st, HAT_K_GATHER, hat_launch_gather(pd, h->b.resid, s.d, c.io_dtype, st));
   LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_table(pd, h->b.inv_freq, h->b.table, s.hd / 2, st));

@@ -56,39 +56,52 @@ __device__ __forceinline__ SegInfo seg_info(const HatPlanDev& p, const HatAttnIt
 
 // Online-softmax update for one 32-key S^T tile held as 16 accumulator values.
 // key of value r: key0 + 8*(r/4) + 4*half + r%4.  Returns probabilities as the
-// two B operands (keys 0..15 / 16..31 of the tile) and rescales O.
-template <int NC>
+// two B operands (keys 0..15 / 16..31 of the tile) and rescales O when the running
+// maximum of any row of the wave moved.  MASK = false is for tiles that lie wholly
+// below every row's causal limit (no compares).  Scores are kept unscaled; the
+// softmax scale (times log2 e) is folded into the exponent's fma.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+template <int NC, bool MASK>
 __device__ __forceinline__ void softmax_step(const f32x16& s_acc, float scale_log2, int key0, int half, int qpos,
                                              float& m_run, float& l_run, f32x16 (&o)[NC], f16x8& p0, f16x8& p1) {
-  float sl[16];
+  float sr[16];
   float mx = -INFINITY;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const int key = key0 + 8 * (r >> 2) + 4 * half + (r & 3);
-    sl[r] = (key <= qpos) ? s_acc[r] * scale_log2 : -INFINITY;
-    mx = fmaxf(mx, sl[r]);
+    if (MASK) {
+      const int key = key0 + 8 * (r >> 2) + 4 * half + (r & 3);
+      sr[r] = (key <= qpos) ? s_acc[r] : -INFINITY;
+    } else {
+      sr[r] = s_acc[r];
+    }
+    mx = fmaxf(mx, sr[r]);
   }
   mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m_run, mx);
+  const float m_new = fmaxf(m_run, mx * scale_log2);   // running maximum in log2 units
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-  const float alpha = exp2f(m_run - m_safe);
   float ps = 0.f;
   float pv[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    pv[r] = exp2f(sl[r] - m_safe);
+    pv[r] = __builtin_amdgcn_exp2f(fmaf(sr[r], scale_log2, -m_safe));
     ps += pv[r];
   }
-  l_run = l_run * alpha + ps;
-  m_run = m_new;
+  if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // wave-uniform: some row's maximum moved
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+    l_run *= alpha;
 #pragma unroll
-  for (int c = 0; c < NC; ++c)
+    for (int c = 0; c < NC; ++c)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[c][r] *= alpha;
+      for (int r = 0; r < 16; ++r) o[c][r] *= alpha;
+    m_run = m_new;
+  }
+  l_run += ps;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    p0[j] = (_Float16)pv[j];
-    p1[j] = (_Float16)pv[8 + j];
+  for (int j = 0; j < 4; ++j) {
+    const f32x2 a = {pv[2 * j], pv[2 * j + 1]}, b = {pv[8 + 2 * j], pv[8 + 2 * j + 1]};
+    const f16x2 ha = __builtin_convertvector(a, f16x2), hb = __builtin_convertvector(b, f16x2);
+    p0[2 * j] = ha[0]; p0[2 * j + 1] = ha[1];
+    p1[2 * j] = hb[0]; p1[2 * j + 1] = hb[1];
   }
 }
 
@@ -195,7 +208,8 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
       }
     }
     f16x8 p0, p1;
-    softmax_step<NC>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+    if (key0 + 31 > sg.start + it.q0) softmax_step<NC, true>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+    else softmax_step<NC, false>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[c], p0, o[c], 0, 0, 0);
@@ -252,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
 
 // ------------------------------------------------------------------ chunk
 template <int HD>
-__global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a) {
+__global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAttn a) {
   constexpr int NS = HD / 16;
   constexpr int NC = HD / 32;
   constexpr int REC = 2 * 16 * HD;        // elements of one (page, head) record
@@ -337,7 +351,8 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(HatPlanDev p, HatAttn a
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kk, qreg[s], sacc, 0, 0, 0);
       }
       f16x8 p0, p1;
-      softmax_step<NC>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+      if (key0 + 31 > sg.start + wq0) softmax_step<NC, true>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+      else softmax_step<NC, false>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
       const bool tail = key0 + 32 > sg.kv_len;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {

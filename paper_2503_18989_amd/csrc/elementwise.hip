@@ -133,53 +133,84 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ resid,
 }
 
 // ---------------------------------------------------------------- RoPE + KV append
-// One thread per (row, head, octet pair): octets o and o + hd/16 hold the two
-// halves of 8 rotation pairs.  q is rotated in place (fp16); rotated k and v are
-// rounded to bf16 and go to the row's (page, slot) of this layer's pool.
+// Two kinds of threads in one launch.
+//  (a) one per (row, head, octet pair): octets o and o + hd/16 hold the two halves of 8
+//      rotation pairs.  q is rotated in place (fp16); rotated k is rounded to bf16 and
+//      written to the row's (page, slot) of this layer's pool as two 16-byte octets.
+//  (b) one per (appended page, head, slot half, octet of v): gathers the octet of the 8
+//      rows whose slots share a lane half, transposes in registers and writes, per
+//      feature, the 8 slots as one 16-byte run of the V tile (whose order is
+//      [feature][slot]); slots that are not new in this step keep their old contents.
 __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const float2* __restrict__ table,
                                    bf16_t* __restrict__ pool, int n_pages, int H, int hd) {
   const int half_oct = hd >> 4;                 // octets per half head
   const int per_row = H * half_oct;
+  const int n_a = p.T * per_row;
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= p.T * per_row) return;
-  const int t = idx / per_row, rem = idx % per_row;
-  const int hh = rem / half_oct, o = rem % half_oct;
   const int d = H * hd, row_len = 3 * d;
-  const int c_lo = hh * hd + o * 8, c_hi = c_lo + (hd >> 1);
-  const float2* cs = table + (size_t)t * (hd >> 1) + o * 8;
+  if (idx < n_a) {
+    // consecutive lanes take consecutive rows of one (head, octet pair): 32 rows of a
+    // P32 panel are one 512-byte run, and consecutive slots of a K tile are contiguous
+    const int t = idx % p.T, rem = idx / p.T;
+    const int hh = rem / half_oct, o = rem % half_oct;
+    const int c_lo = hh * hd + o * 8, c_hi = c_lo + (hd >> 1);
+    const float2* cs = table + (size_t)t * (hd >> 1) + o * 8;
 
-  act_t* q_lo = qkv + p32_index(t, c_lo, row_len);
-  act_t* q_hi = qkv + p32_index(t, c_hi, row_len);
-  const f16x8 ql = *(f16x8*)q_lo, qh = *(f16x8*)q_hi;
-  const f16x8 kl = *(const f16x8*)(qkv + p32_index(t, d + c_lo, row_len));
-  const f16x8 kh = *(const f16x8*)(qkv + p32_index(t, d + c_hi, row_len));
-  const f16x8 vl = *(const f16x8*)(qkv + p32_index(t, 2 * d + c_lo, row_len));
-  const f16x8 vh = *(const f16x8*)(qkv + p32_index(t, 2 * d + c_hi, row_len));
-  f16x8 rql, rqh;
-  bf16x8 rkl, rkh;
+    act_t* q_lo = qkv + p32_index(t, c_lo, row_len);
+    act_t* q_hi = qkv + p32_index(t, c_hi, row_len);
+    const f16x8 ql = *(f16x8*)q_lo, qh = *(f16x8*)q_hi;
+    const f16x8 kl = *(const f16x8*)(qkv + p32_index(t, d + c_lo, row_len));
+    const f16x8 kh = *(const f16x8*)(qkv + p32_index(t, d + c_hi, row_len));
+    f16x8 rql, rqh;
+    bf16x8 rkl, rkh;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float c = cs[e].x, s = cs[e].y;
-    const float a = (float)ql[e], b = (float)qh[e];
-    rql[e] = to_act(a * c - b * s);
-    rqh[e] = to_act(b * c + a * s);
-    const float ka = (float)kl[e], kb = (float)kh[e];
-    rkl[e] = (__bf16)(ka * c - kb * s);
-    rkh[e] = (__bf16)(kb * c + ka * s);
+    for (int e = 0; e < 8; ++e) {
+      const float c = cs[e].x, s = cs[e].y;
+      const float a = (float)ql[e], b = (float)qh[e];
+      rql[e] = to_act(a * c - b * s);
+      rqh[e] = to_act(b * c + a * s);
+      const float ka = (float)kl[e], kb = (float)kh[e];
+      rkl[e] = (__bf16)(ka * c - kb * s);
+      rkh[e] = (__bf16)(kb * c + ka * s);
+    }
+    *(f16x8*)q_lo = rql;
+    *(f16x8*)q_hi = rqh;
+    const int dst = p.kv_dst[t];
+    const int page = dst >> 4, slot = dst & 15;
+    bf16_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
+    *(bf16x8*)(kt + ktile_index(slot, o * 8)) = rkl;
+    *(bf16x8*)(kt + ktile_index(slot, o * 8 + (hd >> 1))) = rkh;
+    return;
   }
-  *(f16x8*)q_lo = rql;
-  *(f16x8*)q_hi = rqh;
-
-  const int dst = p.kv_dst[t];
-  const int page = dst >> 4, slot = dst & 15;
-  bf16_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
-  bf16_t* vt = kt + 16 * hd;
-  *(bf16x8*)(kt + ktile_index(slot, o * 8)) = rkl;
-  *(bf16x8*)(kt + ktile_index(slot, o * 8 + (hd >> 1))) = rkh;
+  const int octs = hd >> 3;
+  const int vidx = idx - n_a;
+  if (vidx >= p.n_append * H * 2 * octs) return;
+  const HatAppendItem it = p.append[vidx % p.n_append];   // consecutive lanes: consecutive pages
+  const int vrem = vidx / p.n_append;
+  const int o = vrem % octs;
+  const int half = (vrem / octs) & 1;
+  const int hh = vrem / (2 * octs);
+  bf16_t* vt = pool + ((size_t)hh * n_pages + it.page) * kv_head_elems(hd) + 16 * hd;
+  f16x8 rows[8];
+  bool valid[8];
+  bool all = true;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int slot = 8 * (j >> 2) + 4 * half + (j & 3);
+    const int pos = it.pos0 + slot;
+    valid[j] = pos >= it.lo && pos < it.hi;
+    all = all && valid[j];
+    if (valid[j]) rows[j] = *(const f16x8*)(qkv + p32_index(it.row0 + slot, 2 * d + hh * hd + o * 8, row_len));
+  }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    vt[vtile_index(slot, o * 8 + e)] = (__bf16)(float)vl[e];
-    vt[vtile_index(slot, o * 8 + (hd >> 1) + e)] = (__bf16)(float)vh[e];
+    bf16_t* dst = vt + vtile_index(4 * half, o * 8 + e);   // j = 0 of this half: 8 slots follow contiguously
+    bf16x8 out;
+    if (!all) out = *(const bf16x8*)dst;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (valid[j]) out[j] = (__bf16)(float)rows[j][e];
+    *(bf16x8*)dst = out;
   }
 }
 
@@ -312,7 +343,7 @@ hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const
 }
 hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, bf16_t* pool_layer,
                                   int n_pages, int H, int hd, hipStream_t st) {
-  const size_t n = (size_t)p.T * H * (hd >> 4);
+  const size_t n = (size_t)p.T * H * (hd >> 4) + (size_t)p.n_append * H * 2 * (hd >> 3);
   rope_append_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, hd);
   return hipGetLastError();
 }

@@ -50,6 +50,15 @@ hipError_t hat_launch_retile(act_t* dst, int Nw, int Kd, const bf16_t* src0, con
 hipError_t hat_launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStream_t st);
 
 // ---- per-step plan as seen by the kernels -----------------------------------
+// One KV page touched by this step's append: rows [lo, hi) of the page's 16 positions are new.
+struct HatAppendItem {
+  int32_t page;   // page id
+  int32_t row0;   // batch row that holds position pos0 (may lie before the segment's first row)
+  int32_t pos0;   // absolute position of the page's slot 0
+  int32_t lo, hi; // new positions of this page: pos0 <= lo < hi <= pos0 + 16
+  int32_t pad0, pad1, pad2;
+};
+
 struct HatPlanDev {
   int T, S;
   const int32_t* pos;       // [T] absolute position of each row
@@ -61,6 +70,8 @@ struct HatPlanDev {
   const int32_t* page_tbl;
   const uint64_t* in_ptr;   // [S] hidden_in
   const uint64_t* out_ptr;  // [S] hidden_out
+  const HatAppendItem* append;  // pages written by this step
+  int n_append;
 };
 
 hipError_t hat_launch_gather(const HatPlanDev& p, float* resid, int d, int io_dtype, hipStream_t st);
