@@ -157,49 +157,81 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // One continuous pipeline over k-steps.  The operands of k-step s+1 are read from LDS
+  // while the MFMAs of k-step s run, also across k-tile boundaries: at the last k-step of
+  // tile i a wave first makes sure tile i+1 has landed (its own loads: vmcnt; everyone's:
+  // barrier -- which also says everyone is done reading tile i), reads tile i+1's first
+  // operands, and only then issues tile i's last MFMAs, with the direct-to-LDS loads of
+  // tile i+NSTAGE (into the buffer tile i just vacated) slotted between those MFMAs.
+  static_assert(KS % 2 == 0, "operand register sets alternate per k-step");
+  static_assert((NSTAGE - 1) * LPW <= 63, "vmcnt is 6 bits");
+  auto issue_chunk = [&](int i, int c) {
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(src[c] + (size_t)i * (BKT / 8) * 256),
+        (__attribute__((address_space(3))) void*)(lds + (i % NSTAGE) * STAGE + wave * (LPW * 1024) + c * 1024), 16, 0, 0);
+  };
+  auto wait_pending = [&](int tiles) {  // at most `tiles` k-tiles of my loads still in flight
+    switch (tiles) {
+      case 0: wait_vmcnt<0>(); break;
+      case 1: wait_vmcnt<(NSTAGE >= 2 ? 1 : 0) * LPW>(); break;
+      case 2: wait_vmcnt<(NSTAGE >= 3 ? 2 : 0) * LPW>(); break;
+      default: wait_vmcnt<(NSTAGE >= 4 ? 3 : 0) * LPW>(); break;
+    }
+  };
+  static_assert(NSTAGE <= 4, "wait_pending covers up to 3 pending tiles");
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
+  for (int s = 0; s < NSTAGE; ++s)
     if (s < nkt) issue(s);
 
   const uint32_t offW = (wf * MI) * SLAB + lane * 16;
   const uint32_t offX = (PF + wt * NJ) * SLAB + lane * 16;
+  f16x8 a[2][MI], bb[2][NJ];
+  constexpr int NMFMA = MI * NJ;
+  constexpr int CPM = (LPW + NMFMA - 1) / NMFMA;  // loads slotted behind each MFMA at a tile boundary
 
-  for (int i = 0; i < nkt; ++i) {
-    // my loads of k-tile i have landed once at most `after` later groups are pending
-    const int after = nkt - 1 - i;
-    if (after >= NSTAGE - 2) {
-      wait_vmcnt<(NSTAGE - 2) * LPW>();
-    } else if (NSTAGE >= 4 && after == NSTAGE - 3) {
-      wait_vmcnt<(NSTAGE >= 4 ? (NSTAGE - 3) * LPW : 0)>();
-    } else if (NSTAGE >= 5 && after == NSTAGE - 4) {
-      wait_vmcnt<(NSTAGE >= 5 ? (NSTAGE - 4) * LPW : 0)>();
-    } else {
-      wait_vmcnt<0>();
-    }
-    __builtin_amdgcn_s_barrier();  // everyone's loads of tile i landed; everyone finished reading tile i-1
-    if (i + NSTAGE - 1 < nkt) issue(i + NSTAGE - 1);
-
-    const uint32_t sbase = lds_base + (i % NSTAGE) * STAGE;
-    const uint32_t aW = sbase + offW, aX = sbase + offX;
-    f16x8 a[2][MI], bb[2][NJ];
+  if (nkt > 0) {
+    wait_pending(nkt - 1 < NSTAGE - 1 ? nkt - 1 : NSTAGE - 1);
+    __builtin_amdgcn_s_barrier();
+    const uint32_t aW = lds_base + offW, aX = lds_base + offX;
     static_for<MI>([&](auto ii) { a[0][ii] = lds_read<ii * SLAB>(aW); });
     static_for<NJ>([&](auto jj) { bb[0][jj] = lds_read<jj * SLAB>(aX); });
+  }
+  for (int i = 0; i < nkt; ++i) {
+    const uint32_t sbase = lds_base + (i % NSTAGE) * STAGE;
+    const uint32_t aW = sbase + offW, aX = sbase + offX;
     static_for<KS>([&](auto ks) {
       constexpr int cur = ks & 1;
       wait_operands(a[cur]);
       wait_operands(bb[cur]);
+      bool refill = false;
       if constexpr (ks + 1 < KS) {
         static_for<MI>([&](auto ii) { a[cur ^ 1][ii] = lds_read<ii * SLAB + (ks + 1) * 1024>(aW); });
         static_for<NJ>([&](auto jj) { bb[cur ^ 1][jj] = lds_read<jj * SLAB + (ks + 1) * 1024>(aX); });
+      } else if (i + 1 < nkt) {
+        const int after = nkt - 2 - i;  // tiles issued behind tile i+1
+        wait_pending(after < NSTAGE - 2 ? after : NSTAGE - 2);
+        __builtin_amdgcn_s_barrier();
+        const uint32_t nbase = lds_base + ((i + 1) % NSTAGE) * STAGE;
+        const uint32_t nW = nbase + offW, nX = nbase + offX;
+        static_for<MI>([&](auto ii) { a[cur ^ 1][ii] = lds_read<ii * SLAB>(nW); });
+        static_for<NJ>([&](auto jj) { bb[cur ^ 1][jj] = lds_read<jj * SLAB>(nX); });
+        refill = (i + NSTAGE < nkt);
       }
-      // keep the next k-step's operand reads ahead of this k-step's MFMAs (the scheduler
-      // would otherwise sink them behind the MFMAs and expose the LDS latency)
+      // keep the operand reads ahead of this k-step's MFMAs (the scheduler would otherwise
+      // sink them behind the MFMAs and expose the LDS latency)
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int ii = 0; ii < MI; ++ii)
-#pragma unroll
-        for (int jj = 0; jj < NJ; ++jj)
-          acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][ii], bb[cur][jj], acc[ii][jj], 0, 0, 0);
+      static_for<NMFMA>([&](auto n) {
+        constexpr int ii = n / NJ, jj = n % NJ;
+        acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][ii], bb[cur][jj], acc[ii][jj], 0, 0, 0);
+        if constexpr (ks + 1 == KS && n * CPM < LPW) {
+          if (refill) {
+            static_for<CPM>([&](auto q) {
+              constexpr int c = n * CPM + q;
+              if constexpr (c < LPW) issue_chunk(i + NSTAGE, c);
+            });
+          }
+        }
+      });
       __builtin_amdgcn_sched_barrier(0);
     });
   }
@@ -281,13 +313,17 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   X(6, 256, 32, 4, 1, 64, 4, EPI)   \
   X(7, 128, 64, 2, 2, 64, 4, EPI)   \
   X(8, 128, 32, 2, 1, 64, 4, EPI)   \
-  X(9, 64, 256, 1, 4, 64, 3, EPI)
-constexpr int kNumTiles = 10;
+  X(9, 64, 256, 1, 4, 64, 3, EPI)   \
+  X(10, 128, 128, 2, 2, 64, 2, EPI) \
+  X(11, 128, 128, 2, 2, 32, 4, EPI) \
+  X(12, 128, 64, 2, 2, 64, 3, EPI)
+constexpr int kNumTiles = 13;
 
 struct TileInfo { int bf, bt, waves, mi; };
 constexpr TileInfo kTiles[kNumTiles] = {{256, 256, 4, 4}, {256, 256, 4, 4}, {128, 256, 4, 2}, {256, 128, 4, 4},
                                         {128, 128, 4, 2}, {256, 64, 4, 2},  {256, 32, 4, 2},  {128, 64, 4, 2},
-                                        {128, 32, 2, 2},  {64, 256, 4, 2}};
+                                        {128, 32, 2, 2},  {64, 256, 4, 2},  {128, 128, 4, 2}, {128, 128, 4, 2},
+                                        {128, 64, 4, 2}};
 
 template <int EPI>
 hipError_t launch_epi(const HatGemm& g, const HatGemmPlan& p, hipStream_t st) {
@@ -343,7 +379,7 @@ HatGemmPlan hat_gemm_plan(const HatGemm& g) {
   double best_cost = 1e300;
   const int KT = g.K / 64;
   for (int c = 0; c < kNumTiles; ++c) {
-    if (c == 1) continue;  // alternative staging of tile 0, selected only when forced
+    if (c == 1 || c >= 10) continue;  // alternative stagings, selected only when forced
     const TileInfo& q = kTiles[c];
     if (g.epilogue == HAT_EPI_SWIGLU && q.mi % 2 != 0) continue;
     const int nT = (g.T + q.bt - 1) / q.bt, nF = g.Nw / q.bf;
