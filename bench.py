@@ -14,6 +14,8 @@ Besides the contract line it reports, in the same JSON object:
   kernels       every kernel class of the step: average duration and roofline
   legs          chunk-attention MFMA fraction on a mixed-batch step and verify-
                 attention HBM GB/s on a verify-heavy step (30 devices)
+  chunk_size_sweep  13B-shaped model, 8 devices x 8192-row prompts, chunk sizes 64..1024:
+                GPU time per step against chunk size and prefix (the cost profile g(.))
   cpu_baseline  the CPU oracle timed on this host on a bounded sample
   paper_context end-to-end numbers the paper reports on other hardware
 """
@@ -213,8 +215,70 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
     return out
 
 
+# ---------------------------------------------------------------- chunk-size sweep (cost profile)
+def chunk_sweep(n_layers, chunks=(64, 128, 256, 512, 1024), n_devices=8, prompt=8192):
+    """13B-shaped middle submodel, 8 devices with 8192-row prompts fed in chunks of c, all
+    devices batched per step (T = 8c rows): GPU time per step against (c, prefix) -- the
+    per-chunk-size cost profile g(.) that the paper's chunk-size rule (Sec. 3.3, Eq. 3) consumes."""
+    import torch
+    from paper_2503_18989_amd import HatMid
+    from paper_2503_18989_amd.binding import CSegment
+    cfg = hi.with_layers(hi.MID13B, n_layers)
+    d = cfg["d_model"]
+    t0 = time.time()
+    weights = gen_weights(cfg, SEED + 5, n_layers)
+    dev_layers = upload(weights)
+    del weights
+    log("13B-shaped weights (%d layers) ready in %.1f s" % (n_layers, time.time() - t0))
+    m = HatMid(cfg, dev_layers, n_pages=n_devices * prompt // 16 + 16, max_devices=n_devices,
+               max_step_tokens=n_devices * max(chunks), max_pos=prompt)
+    del dev_layers
+    torch.cuda.empty_cache()
+    sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    x = to_dev_bf16(hi.hidden_rows(max(chunks), d, SEED + 5, 0))      # the same rows for every device and step
+    out = torch.empty((n_devices, max(chunks), d), dtype=torch.bfloat16, device="cuda")
+    res = []
+    for c in chunks:
+        for dev in range(n_devices):
+            m.release(dev)
+        steps = prompt // c
+        arr = (CSegment * n_devices)()
+        ms = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for j in range(steps):
+            for dev in range(n_devices):
+                arr[dev] = CSegment(dev, hi.CHUNK, c, j * c, x.data_ptr(), out[dev].data_ptr())
+            m.forward_raw(arr, n_devices, sp)
+            if j in (0, steps // 2, steps - 1):
+                ms.append(m.last_step_stats()[1])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        res.append({"chunk": c, "rows_per_step": n_devices * c, "steps": steps, "ms_first_step": ms[0],
+                    "ms_middle_step": ms[1], "ms_last_step": ms[2], "ms_mean_step": dt / steps * 1e3,
+                    "hidden_tokens_per_s": n_devices * prompt / dt})
+        log("sweep c=%d: %.2f ms/step mean (first %.2f, last %.2f), %.0f tokens/s" % (c, dt / steps * 1e3, ms[0], ms[2], n_devices * prompt / dt))
+    m.close()
+    return {"workload": "13B-shaped (%d layers, d 5120, 40x128 heads, FFN 13824), %d devices x %d-row prompts, "
+                        "all devices batched per step" % (n_layers, n_devices, prompt), "points": res}
+
+
+# ---------------------------------------------------------------- measured HBM traffic (from profiles/)
+def recorded_traffic(kernel):
+    """HBM bytes per launch of a kernel class as measured by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+    this benchmark (separate passes; the summary and the commands are in profiles/traffic_cfg2.txt)."""
+    path = os.path.join(ROOT, "profiles", "traffic_cfg2.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel + "_hbm_bytes_per_launch":
+            return float(parts[1])
+    return None
+
+
 # ---------------------------------------------------------------- CPU baseline (oracle)
-def cpu_baseline(cfg7, weights, n_layers=2, n_chunks=4, chunk=256):
+def cpu_baseline(cfg7, weights, n_layers=6, n_chunks=8, chunk=256):
     from oracle import OracleMiddle
     try:
         from threadpoolctl import threadpool_info
@@ -229,7 +293,7 @@ def cpu_baseline(cfg7, weights, n_layers=2, n_chunks=4, chunk=256):
     dt = time.perf_counter() - t0
     scale = cfg7["n_layers"] / n_layers
     return {"value": n_chunks * chunk / (dt * scale), "unit": "hidden tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "first %d of 8 chunks (%d rows) through %d of %d layers in %.1f s, numpy float64; "
+            "sample": "%d of 8 chunks (%d rows) through %d of %d layers in %.1f s, numpy float64; "
                       "extrapolated linearly in layers" % (n_chunks, n_chunks * chunk, n_layers, cfg7["n_layers"], dt)}
 
 
@@ -241,6 +305,10 @@ def main():
     ap.add_argument("--no-legs", action="store_true", help="skip the attention legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--layers", type=int, default=0, help="override depth (for profiling runs; the line is then not the metric)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the 13B-shaped chunk-size sweep")
+    ap.add_argument("--sweep-layers", type=int, default=38, help="depth of the chunk-size sweep model")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling FETCH_SIZE/WRITE_SIZE counters)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the middle-submodel forward on ONE GPU; --gpus %d is not supported "
@@ -290,7 +358,7 @@ def main():
     per_step = {k: v["us_per_launch"] * v["launches_per_step"] for k, v in kernels.items()}
     dom = max((k for k in per_step if "bound" in kernels[k]), key=lambda k: per_step[k])
     roofline = {k: kernels[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
-    roofline.update(kernel=dom, traffic=None, us_per_launch=kernels[dom]["us_per_launch"],
+    roofline.update(kernel=dom, traffic=recorded_traffic(dom), us_per_launch=kernels[dom]["us_per_launch"],
                     algorithmic_bytes=gw[dom][1] if dom in gw else None,
                     algorithmic_flops=gw[dom][0] if dom in gw else None)
     # whole-step roofline: sum over classes of max(flop/peak, bytes/peak), matrix kernels only
@@ -302,6 +370,18 @@ def main():
     legs = None
     if not a.no_legs:
         legs = attention_legs(cfg, dev_layers)
+    if a.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    del dev_layers
+    torch.cuda.empty_cache()
+    sweep = None
+    if not a.no_sweep:
+        sweep = chunk_sweep(a.sweep_layers)
     cpu = None
     if not a.no_cpu:
         cpu = cpu_baseline(cfg, weights)
@@ -317,7 +397,7 @@ def main():
                    "mfma_operands": "fp16 (fp32 accumulate)"},
         "gpu_event_ms_per_step": gpu_s / a.steps * 1e3, "host_wall_ms_per_step": wall / a.steps * 1e3,
         "step_roofline_ms": ideal * 1e3, "step_roofline_frac": ideal / (sec / a.steps),
-        "roofline": roofline, "kernels": kernels, "legs": legs, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "legs": legs, "chunk_size_sweep": sweep, "cpu_baseline": cpu,
         "paper_context": "paper reports end-to-end TTFT -41..54% / TBT -41..77% on 30 Jetson devices + 8xA6000 "
                          "(other hardware, whole system): context only, not a target",
     }
