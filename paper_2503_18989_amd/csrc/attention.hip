@@ -310,8 +310,12 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
   const bf16_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
   const size_t page_stride = REC;
 
-  u32x4 regs[LPT];
-  auto gload = [&](int st) {
+  // K/V stages travel global -> registers -> (widen to fp16) -> LDS.  Two register stages:
+  // the loads of stage st+2 are issued before stage st is computed and are only consumed
+  // (converted and stored to LDS) at the end of stage st+1, so a load has two stage
+  // computations to arrive.
+  u32x4 regsA[LPT], regsB[LPT];
+  auto gload = [&](int st, u32x4 (&regs)[LPT]) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int lin = i * 256 + threadIdx.x;        // 16-byte unit within the stage
@@ -321,20 +325,11 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
       regs[i] = *(const u32x4*)(pool + (size_t)sg.pt[pi] * page_stride + off * 8);
     }
   };
-  auto lstore = [&](int buf) {
+  auto lstore = [&](int buf, u32x4 (&regs)[LPT]) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * 256 + threadIdx.x) * 16]) = kv_to_f16_bits(regs[i]);
   };
-
-  if (st0 < st1) {  // tiles are widened to fp16 once, on their way into LDS
-    gload(st0);
-    lstore(0);
-  }
-  __syncthreads();
-
-  for (int st = st0; st < st1; ++st) {
-    const int buf = (st - st0) & 1;
-    if (st + 1 < st1) gload(st + 1);
+  auto compute = [&](int st, int buf) {
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
       const int key0 = st * 64 + pr * 32;
@@ -366,7 +361,26 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
         o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb, p1, o[c], 0, 0, 0);
       }
     }
-    if (st + 1 < st1) lstore(buf ^ 1);
+  };
+
+  if (st0 < st1) {  // tiles are widened to fp16 once, on their way into LDS
+    gload(st0, regsA);
+    lstore(0, regsA);
+  }
+  if (st0 + 1 < st1) gload(st0 + 1, regsB);
+  __syncthreads();
+
+  for (int st = st0; st < st1; st += 2) {
+    // even step: LDS[0] holds stage st, regsB holds stage st+1, regsA is free
+    if (st + 2 < st1) gload(st + 2, regsA);
+    compute(st, 0);
+    if (st + 1 < st1) lstore(1, regsB);
+    __syncthreads();
+    if (st + 1 >= st1) break;
+    // odd step: LDS[1] holds stage st+1, regsA holds stage st+2, regsB is free
+    if (st + 3 < st1) gload(st + 3, regsB);
+    compute(st + 1, 1);
+    if (st + 2 < st1) lstore(0, regsA);
     __syncthreads();
   }
   l_run += __shfl_xor(l_run, 32);
