@@ -161,8 +161,9 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   // while the MFMAs of k-step s run, also across k-tile boundaries: at the last k-step of
   // tile i a wave first makes sure tile i+1 has landed (its own loads: vmcnt; everyone's:
   // barrier -- which also says everyone is done reading tile i), reads tile i+1's first
-  // operands, and only then issues tile i's last MFMAs, with the direct-to-LDS loads of
-  // tile i+NSTAGE (into the buffer tile i just vacated) slotted between those MFMAs.
+  // operands, and only then issues tile i's last MFMAs.  The direct-to-LDS loads of tile
+  // i+NSTAGE (into the buffer tile i just vacated) are slotted between the MFMAs of the
+  // following KS k-steps.
   static_assert(KS % 2 == 0, "operand register sets alternate per k-step");
   static_assert((NSTAGE - 1) * LPW <= 63, "vmcnt is 6 bits");
   auto issue_chunk = [&](int i, int c) {
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   const uint32_t offX = (PF + wt * NJ) * SLAB + lane * 16;
   f16x8 a[2][MI], bb[2][NJ];
   constexpr int NMFMA = MI * NJ;
-  constexpr int CPM = (LPW + NMFMA - 1) / NMFMA;  // loads slotted behind each MFMA at a tile boundary
+  constexpr int CPP = (LPW + KS - 1) / KS;  // loads of one refill part (one k-step's share of a tile)
 
   if (nkt > 0) {
     wait_pending(nkt - 1 < NSTAGE - 1 ? nkt - 1 : NSTAGE - 1);
@@ -203,7 +204,6 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
       constexpr int cur = ks & 1;
       wait_operands(a[cur]);
       wait_operands(bb[cur]);
-      bool refill = false;
       if constexpr (ks + 1 < KS) {
         static_for<MI>([&](auto ii) { a[cur ^ 1][ii] = lds_read<ii * SLAB + (ks + 1) * 1024>(aW); });
         static_for<NJ>([&](auto jj) { bb[cur ^ 1][jj] = lds_read<jj * SLAB + (ks + 1) * 1024>(aX); });
@@ -215,22 +215,28 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
         const uint32_t nW = nbase + offW, nX = nbase + offX;
         static_for<MI>([&](auto ii) { a[cur ^ 1][ii] = lds_read<ii * SLAB>(nW); });
         static_for<NJ>([&](auto jj) { bb[cur ^ 1][jj] = lds_read<jj * SLAB>(nX); });
-        refill = (i + NSTAGE < nkt);
       }
+      // The refill of the ring is spread thinly over the MFMAs: a direct-to-LDS load holds
+      // the issuing wave for on the order of a hundred cycles, so a burst of them would
+      // stall the matrix pipe.  The tile going into the buffer vacated at the last
+      // boundary is issued in KS parts: part 0 right after that boundary (last k-step of
+      // the previous tile), parts 1.. over this tile's k-steps 0..KS-2.
+      constexpr int part = (ks + 1) % KS;
+      const int rtile = (ks + 1 == KS) ? i + NSTAGE : i - 1 + NSTAGE;
+      const bool refill = rtile < nkt && ((ks + 1 == KS) ? (i + 1 < nkt) : (i >= 1));
       // keep the operand reads ahead of this k-step's MFMAs (the scheduler would otherwise
       // sink them behind the MFMAs and expose the LDS latency)
       __builtin_amdgcn_sched_barrier(0);
       static_for<NMFMA>([&](auto n) {
         constexpr int ii = n / NJ, jj = n % NJ;
         acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[cur][ii], bb[cur][jj], acc[ii][jj], 0, 0, 0);
-        if constexpr (ks + 1 == KS && n * CPM < LPW) {
-          if (refill) {
-            static_for<CPM>([&](auto q) {
-              constexpr int c = n * CPM + q;
-              if constexpr (c < LPW) issue_chunk(i + NSTAGE, c);
-            });
+        static_for<CPP>([&](auto q) {
+          constexpr int slot = (q * NMFMA / CPP) < NMFMA ? (q * NMFMA / CPP) : NMFMA - 1;
+          constexpr int c = part * CPP + q;
+          if constexpr (slot == n && c < LPW) {
+            if (refill) issue_chunk(rtile, c);
           }
-        }
+        });
       });
       __builtin_amdgcn_sched_barrier(0);
     });
