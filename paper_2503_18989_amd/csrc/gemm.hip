@@ -322,14 +322,19 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   X(9, 64, 256, 1, 4, 64, 3, EPI)   \
   X(10, 128, 128, 2, 2, 64, 2, EPI) \
   X(11, 128, 128, 2, 2, 32, 4, EPI) \
-  X(12, 128, 64, 2, 2, 64, 3, EPI)
-constexpr int kNumTiles = 13;
+  X(12, 128, 64, 2, 2, 64, 3, EPI)  \
+  X(13, 256, 256, 4, 2, 32, 4, EPI) \
+  X(14, 128, 256, 2, 4, 64, 3, EPI) \
+  X(15, 256, 128, 4, 2, 64, 3, EPI) \
+  X(16, 256, 256, 2, 4, 32, 4, EPI)
+constexpr int kNumTiles = 17;
 
 struct TileInfo { int bf, bt, waves, mi; };
 constexpr TileInfo kTiles[kNumTiles] = {{256, 256, 4, 4}, {256, 256, 4, 4}, {128, 256, 4, 2}, {256, 128, 4, 4},
                                         {128, 128, 4, 2}, {256, 64, 4, 2},  {256, 32, 4, 2},  {128, 64, 4, 2},
                                         {128, 32, 2, 2},  {64, 256, 4, 2},  {128, 128, 4, 2}, {128, 128, 4, 2},
-                                        {128, 64, 4, 2}};
+                                        {128, 64, 4, 2},  {256, 256, 8, 2}, {128, 256, 8, 2}, {256, 128, 8, 2},
+                                        {256, 256, 8, 4}};
 
 template <int EPI>
 hipError_t launch_epi(const HatGemm& g, const HatGemmPlan& p, hipStream_t st) {
