@@ -11,9 +11,11 @@
 // of the P32 layout of the *next* operand, so every epilogue stores coalesced.
 //
 // Data movement: global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4),
-// no register staging, into a ring of NSTAGE stages, so NSTAGE-1 k-tiles are in
-// flight while one is multiplied -- the weight stream of a small-batch step comes
-// from HBM and needs about a microsecond of loads in flight per CU.  Because the
+// no register staging, into a ring of NSTAGE k-tiles.  Measured on MI355X: a CU
+// sustains about 36-42 B/clk through these loads, each one holds the issuing wave
+// for on the order of a hundred cycles, and the ring depth beyond two tiles does not
+// matter -- so the refill is spread thinly between the MFMAs instead of issued in
+// bursts, and the tile shape (bytes moved per flop) decides the rest.  Because the
 // P32 panel slab of a k-tile is contiguous in memory and is kept contiguous in
 // LDS, each wave instruction moves one 1 KB run, and an MFMA operand is one
 // ds_read_b128 at lane*16 + immediate, conflict-free without a swizzle.
@@ -387,10 +389,13 @@ HatGemmPlan hat_gemm_plan(const HatGemm& g) {
     if (g.epilogue == HAT_EPI_SWIGLU && kTiles[best.tile].mi % 2 != 0) best.tile = 0;
     return best;
   }
+  // Constants fitted to tile sweeps on MI355X at T = 150 .. 3556 (7B shapes): a CU moves
+  // about 36 B/clk through direct-to-LDS loads, the MFMA loop runs at about 85 % of the
+  // matrix peak on its own, and the two overlap only partly (issuing the loads holds
+  // the waves that also issue the MFMAs); the weight stream cannot beat ~5.5 TB/s.
   double best_cost = 1e300;
   const int KT = g.K / 64;
-  for (int c = 0; c < kNumTiles; ++c) {
-    if (c == 1 || c >= 10) continue;  // alternative stagings, selected only when forced
+  for (int c = 1; c < 10; ++c) {  // tile 0 and tiles >= 10 are alternative stagings, used only when forced
     const TileInfo& q = kTiles[c];
     if (g.epilogue == HAT_EPI_SWIGLU && q.mi % 2 != 0) continue;
     const int nT = (g.T + q.bt - 1) / q.bt, nF = g.Nw / q.bf;
@@ -399,12 +404,14 @@ HatGemmPlan hat_gemm_plan(const HatGemm& g) {
       if (ks > 1 && (KT / ks < 4 || (long)ks * g.T > g.part_rows)) break;
       const double blocks = (double)nT * nF * ks;
       const double rounds = std::ceil(blocks / 256.0);
-      const double kt = std::ceil((double)KT / ks) + 2.0;              // + pipeline fill
-      const double mfma_cyc = 2.0 * q.bf * q.bt * 64 / (4 * 1017.0);   // per k-tile, 4 SIMDs
-      const double load_cyc = (q.bf + q.bt) * 64 * 2 / 48.0;           // per k-tile at ~48 B/clk/CU
-      double cost = rounds * kt * std::max(mfma_cyc, load_cyc) * (q.waves == 4 ? 1.0 : 1.5);
-      cost += rounds * 1500.0;                                          // launch/epilogue per round
-      if (ks > 1) cost += (double)ks * g.T * g.Nout * 8.0 / 256.0 / 32.0;  // partial write+read, per CU
+      const double kt = std::ceil((double)KT / ks) + 2.0;                     // + pipeline fill
+      const double mfma_cyc = 2.0 * q.bf * q.bt * 64 / (4 * 1017.0 * 0.85);   // per k-tile, 4 SIMDs
+      const double load_cyc = (q.bf + q.bt) * 64 * 2 / 36.0;                  // per k-tile
+      const double tile_cyc = std::max(mfma_cyc, load_cyc) + 0.45 * std::min(mfma_cyc, load_cyc);
+      double cyc = rounds * kt * tile_cyc * (q.waves == 4 ? 1.0 : 1.5) + rounds * 3000.0;
+      if (ks > 1) cyc += (double)ks * g.T * g.Nout * 8.0 / 256.0 / 24.0;      // partial write + read, per CU
+      const double hbm_cyc = 2.0 * g.Nw * g.K / 5.5e12 * 2.4e9 + 7000.0;
+      const double cost = std::max(cyc, hbm_cyc) + 1e-3 * cyc;                // tie-break below the HBM floor
       if (cost < best_cost) { best_cost = cost; best.tile = c; best.ksplit = ks; }
     }
   }
