@@ -117,7 +117,19 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
     const int x = b % 8, i = b / 8;
     b = x * per + (x < rem ? x : rem) + i;
   }
-  const int ft = b / nT, tt = b % nT;
+  // within an XCD's run, walk groups of 4 feature tiles across the token tiles: the ~32
+  // workgroups resident on an XCD then form a 4 x 8 patch of tiles (12 distinct operand
+  // slabs per k-tile instead of 16+) and more of their loads hit in L2
+  int ft, tt;
+  {
+    constexpr int GF = 4;
+    const int grp = b / (GF * nT);
+    const int f0 = grp * GF;
+    const int gf = (nF - f0) < GF ? (nF - f0) : GF;
+    const int r = b - grp * GF * nT;
+    ft = f0 + r % gf;
+    tt = r / gf;
+  }
   const int Tpanels = (g.T + 31) >> 5;
 
   const int KT = g.K / BKT;
