@@ -213,6 +213,10 @@ hat_status_t hat_mid_debug_dump(hat_mid_t* h, int32_t which, void* dst, void* hi
  * beyond fp32 summation order. */
 hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile, int32_t ksplit);
 
+/* Number of entries in the library's GEMM tile table (valid `tile` values of
+ * hat_mid_debug_force_gemm are 0 .. count-1).  No GPU work. */
+int32_t hat_mid_debug_gemm_tile_count(void);
+
 #ifdef __cplusplus
 }
 #endif

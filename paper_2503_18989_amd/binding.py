@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = [
     "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_release",
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_import", "hat_mid_kv_export",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
+    "hat_mid_debug_gemm_tile_count",
 ]
 
 
@@ -97,6 +98,8 @@ def load_library():
     lib.hat_mid_debug_dump.argtypes = [vp, i32, vp, vp]
     lib.hat_mid_debug_force_gemm.restype = i32
     lib.hat_mid_debug_force_gemm.argtypes = [vp, i32, i32, i32]
+    lib.hat_mid_debug_gemm_tile_count.restype = i32
+    lib.hat_mid_debug_gemm_tile_count.argtypes = []
     _LIB = lib
     return lib
 
@@ -226,6 +229,9 @@ class HatMid:
 
     def force_gemm(self, which, tile, ksplit=1):
         self._check(self.lib.hat_mid_debug_force_gemm(self._handle, which, tile, ksplit))
+
+    def gemm_tile_count(self):
+        return int(self.lib.hat_mid_debug_gemm_tile_count())
 
     def close(self):
         if getattr(self, "_handle", None) is not None and self._handle.value:

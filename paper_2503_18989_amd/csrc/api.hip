@@ -738,6 +738,8 @@ hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile,
   return HAT_OK;
 }
 
+int32_t hat_mid_debug_gemm_tile_count(void) { return hat_gemm_tile_count(); }
+
 hat_status_t hat_mid_debug_dump(hat_mid_t* h, int32_t which, void* dst, void* hip_stream) {
   if (!h || !dst) return HAT_EINVAL;
   if (!h->have_step) return fail(h, HAT_EINVAL, "no step has run yet");

@@ -233,9 +233,10 @@ __global__ void retile_kernel(act_t* __restrict__ dst, int Nw, int Kd, const bf1
   } else if (mode == 1) {
     if (R < 3 * n0) { src = R < n0 ? s0 : R < 2 * n0 ? s1 : s2; sr = R % n0; }
   } else {
-    const int blk = R >> 6, w = R & 63;
-    const int f = blk * 32 + (w & 31);
-    if (f < n0) { src = (w < 32) ? s0 : s1; sr = f; }
+    // gate/up: every 32-row block = 16 gate rows, then the up rows of the same 16 features
+    const int blk = R >> 5, w = R & 31;
+    const int f = blk * 16 + (w & 15);
+    if (f < n0) { src = (w < 16) ? s0 : s1; sr = f; }
   }
   bf16x8 v;
 #pragma unroll

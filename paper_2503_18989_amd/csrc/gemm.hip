@@ -25,6 +25,7 @@
 // have", lgkmcnt for the operand reads.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <type_traits>
 #include <utility>
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   // give each XCD a contiguous run of tiles so that tiles sharing a weight panel
   // meet in one L2.
   const int nT = (g.T + BT - 1) / BT;
-  const int nF = g.Nw / BF;
+  const int nF = (g.Nw + BF - 1) / BF;
   const int nblk = nT * nF;
   int b = blockIdx.x;
   {
@@ -146,7 +147,9 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
     const int q = ch / CPS, sub = ch % CPS;
     const act_t* base;
     if (q < PF) {
-      base = g.W + (size_t)(ft * PF + q) * krow;
+      int pnl = ft * PF + q;
+      pnl = pnl < (g.Nw >> 5) ? pnl : (g.Nw >> 5) - 1;  // ragged last feature tile: same
+      base = g.W + (size_t)pnl * krow;
     } else {
       int pnl = tt * PT + (q - PF);
       pnl = pnl < Tpanels ? pnl : Tpanels - 1;  // ragged last tile: re-read a real panel
@@ -279,19 +282,20 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
         }
       }
     } else if constexpr (EPI == HAT_EPI_SWIGLU) {
-      if constexpr (MI % 2 == 0) {
+      // a 32-row block of W holds 16 gate rows then the 16 up rows of the same features:
+      // accumulator elements 4q+e (q = 0,1) and 4(q+2)+e of a lane are gate and up of
+      // output feature fb + 8q + 4h + e
 #pragma unroll
-        for (int i = 0; i < MI; i += 2) {
-          const int fb = (f_base + i * 32) / 2;  // output feature block
-          if (fb >= g.Nout) continue;
+      for (int i = 0; i < MI; ++i) {
+        const int fb = (f_base + i * 32) / 2;  // output feature block (16 wide)
+        if (fb >= g.Nout) continue;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int f = fb + 8 * q + 4 * h;
-            f16x4 v;
+        for (int q = 0; q < 2; ++q) {
+          const int f = fb + 8 * q + 4 * h;
+          f16x4 v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = to_act(silu_f(acc[i][j][4 * q + e]) * acc[i + 1][j][4 * q + e]);
-            *(f16x4*)(g.outP + p32_index(tok, f, g.Nout)) = v;
-          }
+          for (int e = 0; e < 4; ++e) v[e] = to_act(silu_f(acc[i][j][4 * q + e]) * acc[i][j][4 * (q + 2) + e]);
+          *(f16x4*)(g.outP + p32_index(tok, f, g.Nout)) = v;
         }
       }
     } else {
@@ -322,7 +326,9 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   }
 }
 
-// tile table: id, features x tokens, waves along features x tokens, k per stage, stages
+// tile table: id, features x tokens, waves along features x tokens, k per stage, stages.
+// Heights of 96 and 192 rows exist so that the tile count can match the 256 CUs where
+// 128 / 256 leave a quarter or a third of them idle (7B-shaped QKV and gate/up at T <= 256).
 #define HAT_FOR_TILES(X, EPI)       \
   X(0, 256, 256, 2, 2, 64, 2, EPI)  \
   X(1, 256, 256, 2, 2, 32, 4, EPI)  \
@@ -337,26 +343,31 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   X(10, 128, 128, 2, 2, 64, 2, EPI) \
   X(11, 128, 128, 2, 2, 32, 4, EPI) \
   X(12, 128, 64, 2, 2, 64, 3, EPI)  \
-  X(13, 256, 256, 4, 2, 32, 4, EPI) \
-  X(14, 128, 256, 2, 4, 64, 3, EPI) \
-  X(15, 256, 128, 4, 2, 64, 3, EPI) \
-  X(16, 256, 256, 2, 4, 32, 4, EPI)
-constexpr int kNumTiles = 17;
+  X(13, 192, 128, 2, 2, 64, 3, EPI) \
+  X(14, 96, 128, 1, 4, 64, 4, EPI)  \
+  X(15, 96, 256, 1, 4, 64, 3, EPI)  \
+  X(16, 192, 64, 2, 2, 64, 4, EPI)  \
+  X(17, 192, 256, 2, 2, 64, 2, EPI) \
+  X(18, 96, 64, 1, 2, 64, 4, EPI)
+constexpr int kNumTiles = 19;
 
-struct TileInfo { int bf, bt, waves, mi; };
-constexpr TileInfo kTiles[kNumTiles] = {{256, 256, 4, 4}, {256, 256, 4, 4}, {128, 256, 4, 2}, {256, 128, 4, 4},
-                                        {128, 128, 4, 2}, {256, 64, 4, 2},  {256, 32, 4, 2},  {128, 64, 4, 2},
-                                        {128, 32, 2, 2},  {64, 256, 4, 2},  {128, 128, 4, 2}, {128, 128, 4, 2},
-                                        {128, 64, 4, 2},  {256, 256, 8, 2}, {128, 256, 8, 2}, {256, 128, 8, 2},
-                                        {256, 256, 8, 4}};
+struct TileInfo { int bf, bt, waves, bkt, nstage; bool planned; };
+// `planned`: offered to the automatic choice; the others are alternative stagings of the
+// same shapes, used only when forced
+constexpr bool kPlanned[kNumTiles] = {false, true, true, true, true, true, true, true, true, true,
+                                      false, false, false, true, true, true, true, true, true};
+constexpr TileInfo kTiles[kNumTiles] = {
+#define HAT_INFO(id, bf, bt, wf, wt, bkt, ns, epi) {bf, bt, (wf) * (wt), bkt, ns, kPlanned[id]},
+    HAT_FOR_TILES(HAT_INFO, 0)
+#undef HAT_INFO
+};
 
 template <int EPI>
 hipError_t launch_epi(const HatGemm& g, const HatGemmPlan& p, hipStream_t st) {
 #define HAT_TRY(id, bf, bt, wf, wt, bkt, ns, epi)                       \
   if (p.tile == id) {                                                   \
     using TL = Tile<bf, bt, wf, wt, bkt, ns>;                           \
-    if (epi == HAT_EPI_SWIGLU && TL::MI % 2 != 0) return hipErrorInvalidValue; \
-    dim3 grid(((g.T + bt - 1) / bt) * (g.Nw / bf), 1, p.ksplit);        \
+    dim3 grid(((g.T + bt - 1) / bt) * ((g.Nw + bf - 1) / bf), 1, p.ksplit); \
     auto kern = gemm_kernel<bf, bt, wf, wt, bkt, ns, epi>;              \
     kern<<<grid, dim3(wf * wt * 64), TL::LDS_BYTES, st>>>(g, p.ksplit); \
     return hipGetLastError();                                           \
@@ -380,6 +391,8 @@ hipError_t attr_epi() {
 
 }  // namespace
 
+int hat_gemm_tile_count() { return kNumTiles; }
+
 hipError_t hat_gemm_init() {
   hipError_t e;
   if ((e = attr_epi<HAT_EPI_P32>()) != hipSuccess) return e;
@@ -398,20 +411,24 @@ HatGemmPlan hat_gemm_plan(const HatGemm& g) {
     best.ksplit = g.force_ksplit > 0 ? g.force_ksplit : 1;
     if (g.epilogue != HAT_EPI_RESID || !g.part) best.ksplit = 1;
     while (best.ksplit > 1 && ((long)best.ksplit * g.T > g.part_rows || g.K / 64 / best.ksplit < 1)) --best.ksplit;
-    if (g.epilogue == HAT_EPI_SWIGLU && kTiles[best.tile].mi % 2 != 0) best.tile = 0;
     return best;
   }
-  // Constants fitted to tile sweeps on MI355X at T = 150 .. 3556 (7B shapes): a CU moves
+  // Constants fitted to tile sweeps on MI355X at T = 32 .. 3556 (7B shapes): a CU moves
   // about 36 B/clk through direct-to-LDS loads, the MFMA loop runs at about 85 % of the
   // matrix peak on its own, and the two overlap only partly (issuing the loads holds
-  // the waves that also issue the MFMAs); the weight stream cannot beat ~5.5 TB/s.
+  // the waves that also issue the MFMAs).  The weight stream cannot beat ~5.5 TB/s, nor
+  // (Little's law) the bytes of W that the resident workgroups' rings keep in flight
+  // divided by the ~1.2 us a load from HBM takes under load -- which is what decides
+  // between shapes when there are few token rows.
   double best_cost = 1e300;
   const int KT = g.K / 64;
-  for (int c = 1; c < 10; ++c) {  // tile 0 and tiles >= 10 are alternative stagings, used only when forced
+  for (int c = 0; c < kNumTiles; ++c) {
     const TileInfo& q = kTiles[c];
-    if (g.epilogue == HAT_EPI_SWIGLU && q.mi % 2 != 0) continue;
-    const int nT = (g.T + q.bt - 1) / q.bt, nF = g.Nw / q.bf;
+    if (!q.planned) continue;
+    const int nT = (g.T + q.bt - 1) / q.bt, nF = (g.Nw + q.bf - 1) / q.bf;
     const int max_split = (g.epilogue == HAT_EPI_RESID && g.part) ? 16 : 1;
+    const int lds = q.nstage * (q.bf + q.bt) * q.bkt * 2;
+    const int per_cu = std::max(1, std::min(160 * 1024 / lds, 8 / q.waves));
     for (int ks = 1; ks <= max_split; ++ks) {
       if (ks > 1 && (KT / ks < 4 || (long)ks * g.T > g.part_rows)) break;
       const double blocks = (double)nT * nF * ks;
@@ -420,9 +437,12 @@ HatGemmPlan hat_gemm_plan(const HatGemm& g) {
       const double mfma_cyc = 2.0 * q.bf * q.bt * 64 / (4 * 1017.0 * 0.85);   // per k-tile, 4 SIMDs
       const double load_cyc = (q.bf + q.bt) * 64 * 2 / 36.0;                  // per k-tile
       const double tile_cyc = std::max(mfma_cyc, load_cyc) + 0.45 * std::min(mfma_cyc, load_cyc);
-      double cyc = rounds * kt * tile_cyc * (q.waves == 4 ? 1.0 : 1.5) + rounds * 3000.0;
-      if (ks > 1) cyc += (double)ks * g.T * g.Nout * 8.0 / 256.0 / 24.0;      // partial write + read, per CU
-      const double hbm_cyc = 2.0 * g.Nw * g.K / 5.5e12 * 2.4e9 + 7000.0;
+      double cyc = rounds * kt * tile_cyc + rounds * 3000.0;
+      if (ks > 1) cyc += (double)ks * g.T * g.Nout * 8.0 / 256.0 / 12.0;      // partial write + read, per CU
+      const double resident = std::min(blocks, 256.0 * per_cu);
+      const double inflight = resident * q.bf * q.bkt * 2.0 * (q.nstage - 1);
+      const double bw = std::min(5.5e12, inflight / 1.2e-6);
+      const double hbm_cyc = 2.0 * g.Nw * g.K / bw * 2.4e9 + 7000.0;
       const double cost = std::max(cyc, hbm_cyc) + 1e-3 * cyc;                // tie-break below the HBM floor
       if (cost < best_cost) { best_cost = cost; best.tile = c; best.ksplit = ks; }
     }

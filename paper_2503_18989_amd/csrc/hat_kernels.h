@@ -13,7 +13,7 @@ constexpr int HAT_MAX_VERIFY_ROWS = 8;  // query rows of a verify work item
 // ---- GEMM: out[t, f] = sum_k X[t, k] * W[f, k], operands in P32 layout ------
 enum HatEpilogue {
   HAT_EPI_P32 = 0,     // bf16 result, P32 layout, row length Nout
-  HAT_EPI_SWIGLU = 1,  // W rows interleaved (32 gate, 32 up): silu(gate)*up, P32, row length Nout
+  HAT_EPI_SWIGLU = 1,  // W rows interleaved (16 gate, 16 up): silu(gate)*up, P32, row length Nout
   HAT_EPI_RESID = 2    // resid[t, f] += result  (fp32 row-major, leading dim Nout)
 };
 
@@ -38,6 +38,7 @@ struct HatGemmPlan {
 };
 HatGemmPlan hat_gemm_plan(const HatGemm& g);
 hipError_t hat_launch_gemm(const HatGemm& g, const HatGemmPlan& p, hipStream_t st);
+int hat_gemm_tile_count();
 hipError_t hat_gemm_init();  // one-time function attributes (dynamic LDS size)
 
 // ---- weight re-tiling (create time) -----------------------------------------

@@ -75,6 +75,28 @@ def test_ragged_row_counts_cover_every_gemm_tile(T):
     p.close()
 
 
+@pytest.mark.parametrize("T", [70, 300])
+def test_every_gemm_tile_forced(T):
+    # every entry of the tile table on every GEMM class, with and without a K split where the
+    # class allows one; the weight rows (768 / 512 / 1536 / 256 after padding) are not multiples
+    # of the 96- and 192-row tiles, so their ragged last feature tile is covered as well
+    p = Pair(SMALL64, 12, n_pages=64, max_devices=2, max_step_tokens=512, max_pos=1024)
+    x = hi.hidden_rows(T, 256, 12, 0, 0)
+    ref = p.ref.forward([(0, 0, x)])[0]
+    xd = to_dev_bf16(x)
+    n_tiles = p.gpu.gemm_tile_count()
+    assert n_tiles >= 10
+    from paper_2503_18989_amd import Segment
+    for tile in range(n_tiles):
+        for ks in (1, 2):
+            for which in range(4):
+                p.gpu.force_gemm(which, tile, ks)
+            out = to_np(p.gpu.forward([Segment(0, hi.CHUNK, 0, xd)])[0])
+            e = rel_err(out, ref)
+            assert np.all(np.isfinite(out)) and e <= TOL, "tile %d ksplit %d: rel err %.3e" % (tile, ks, e)
+    p.close()
+
+
 @pytest.mark.parametrize("cfg", [SMALL64, SMALL128], ids=["hd64", "hd128"])
 def test_mixed_ragged_batches_with_rollback(cfg):
     p = Pair(cfg, 21, n_pages=200, max_devices=8, max_step_tokens=1024, max_pos=2048)
