@@ -124,7 +124,8 @@ hat_status_t hat_mid_create(const hat_mid_config_t* cfg, const hat_mid_layer_wei
  * every segment the n output rows are written to hidden_out.  KV rows of the new
  * tokens are appended to each device's cache; pages follow the fixed policy
  * "lowest free id first; all rollback frees of the step, in array order, then
- * allocations in array order".  Atomic on error. */
+ * allocations in array order".  Atomic on error.  n_segs == 0 is an empty step:
+ * HAT_OK, nothing is enqueued and no state changes (segs may be NULL then). */
 hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream);
 
 /* The device left (Sec. 2.1: requests leave the batch): all its pages return to

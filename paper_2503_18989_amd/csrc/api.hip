@@ -368,7 +368,8 @@ hat_status_t hat_mid_kv_query(const hat_mid_t* h, int32_t device_id, int32_t* kv
 
 hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
   if (!h) return HAT_EINVAL;
-  if (!segs || n_segs <= 0) return fail(h, HAT_EINVAL, "no segments");
+  if (n_segs == 0) return HAT_OK;  // an empty step: no work, no state change
+  if (!segs || n_segs < 0) return fail(h, HAT_EINVAL, "no segments");
   const hat_mid_config_t& c = h->cfg;
   const Shapes& s = h->s;
   hipStream_t st = (hipStream_t)hip_stream;

@@ -24,6 +24,7 @@
 // that attn_merge combines.
 #include <hip/hip_runtime.h>
 
+#include "hat_device_util.h"
 #include "hat_kernels.h"
 #include "hat_layout.h"
 
@@ -265,6 +266,33 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
 }
 
 // ------------------------------------------------------------------ chunk
+// softmax_step in two parts, for the interior stages of the chunk kernel where the
+// matrix pipe should stay busy while the VALU does the exponentials: scores -> (maximum,
+// exponentials, row sum) touches only the score registers, so it can be scheduled among the
+// MFMAs that still accumulate into O; the O rescale and the fp16 pack follow.
+__device__ __forceinline__ void softmax_probs(f32x16& s, float scale_log2, float m_run, float& m_new, float& ps) {
+  float mx = s[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  m_new = fmaxf(m_run, mx * scale_log2);
+  ps = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2, -m_new));  // scores are finite here: m_new is too
+    ps += s[r];
+  }
+}
+__device__ __forceinline__ void probs_to_f16(const f32x16& pv, f16x8& p0, f16x8& p1) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const f32x2 a = {pv[2 * j], pv[2 * j + 1]}, b = {pv[8 + 2 * j], pv[8 + 2 * j + 1]};
+    const f16x2 ha = __builtin_convertvector(a, f16x2), hb = __builtin_convertvector(b, f16x2);
+    p0[2 * j] = ha[0]; p0[2 * j + 1] = ha[1];
+    p1[2 * j] = hb[0]; p1[2 * j + 1] = hb[1];
+  }
+}
+
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAttn a) {
   constexpr int NS = HD / 16;
@@ -277,7 +305,8 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
   const HatAttnItem it = a.items[blockIdx.x];
   const int head = blockIdx.y;
   const SegInfo sg = seg_info(p, it);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: per-wave decisions become scalar branches
   const int half = lane >> 5, n = lane & 31;
   const int wq0 = it.q0 + 32 * wave;  // first row of this wave, relative to the segment
   int nq_w = it.nq - 32 * wave;       // valid rows of this wave
@@ -288,6 +317,7 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
   const int qrow = sg.tok0 + qi;
   const int qpos = sg.start + qi;
   const int wave_last_pos = wave_live ? sg.start + wq0 + nq_w - 1 : -1;
+  const int wave_first_pos = sg.start + wq0;
   const float scale_log2 = kLog2e / sqrtf((float)HD);
 
   f16x8 qreg[NS];
@@ -310,25 +340,38 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
   const bf16_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
   const size_t page_stride = REC;
 
-  // K/V stages travel global -> registers -> (widen to fp16) -> LDS.  Two register stages:
-  // the loads of stage st+2 are issued before stage st is computed and are only consumed
-  // (converted and stored to LDS) at the end of stage st+1, so a load has two stage
-  // computations to arrive.
-  u32x4 regsA[LPT], regsB[LPT];
-  auto gload = [&](int st, u32x4 (&regs)[LPT]) {
+  // K/V stages travel global -> registers -> (widen to fp16) -> LDS.  The loads of stage
+  // st+2 are issued during stage st, right after the registers gave stage st+1 to LDS,
+  // and are consumed one whole stage later.
+  u32x4 regs[LPT];
+  constexpr int UPR = RECB / 16;  // 16-byte units per (page, head) record
+  static_assert(LPT == NS && (256 % UPR == 0 || UPR % 256 == 0), "a thread's i-th unit lies in page (i*256)/UPR for every thread");
+  const uint32_t lane_off = threadIdx.x * 16;
+  int pgid[4];  // page ids of the stage to load next (the same for every thread)
+  auto load_page_ids = [&](int st) {
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const int lin = i * 256 + threadIdx.x;        // 16-byte unit within the stage
-      const int pg = lin / (RECB / 16), off = lin % (RECB / 16);
-      int pi = st * 4 + pg;
+    for (int k = 0; k < 4; ++k) {
+      int pi = st * 4 + k;
       pi = pi < sg.npages ? pi : sg.npages - 1;
-      regs[i] = *(const u32x4*)(pool + (size_t)sg.pt[pi] * page_stride + off * 8);
+      pgid[k] = sg.pt[pi];
     }
   };
-  auto lstore = [&](int buf, u32x4 (&regs)[LPT]) {
+  auto gload_one = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    constexpr int pg = (i * 256) / UPR, off0 = (i * 256) % UPR;  // same page for the whole workgroup
+    const int page = __builtin_amdgcn_readfirstlane(pgid[pg]);
+    const unsigned char* rec = (const unsigned char*)pool + (size_t)page * RECB;  // wave-uniform
+    regs[i] = *(const u32x4*)(rec + lane_off + off0 * 16);
+  };
+  auto gload = [&](int st) {
+    load_page_ids(st);
+    hat_static_for<LPT>([&](auto ic) { gload_one(ic); });
+  };
+  auto lstore = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * 256 + threadIdx.x) * 16]) = kv_to_f16_bits(regs[i]);
   };
+  // general stage: causal masks, ragged ends, waves that skip a 32-key half
   auto compute = [&](int st, int buf) {
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
@@ -346,7 +389,7 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kk, qreg[s], sacc, 0, 0, 0);
       }
       f16x8 p0, p1;
-      if (key0 + 31 > sg.start + wq0) softmax_step<NC, true>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+      if (key0 + 31 > wave_first_pos) softmax_step<NC, true>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
       else softmax_step<NC, false>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
       const bool tail = key0 + 32 > sg.kv_len;
 #pragma unroll
@@ -362,25 +405,150 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
       }
     }
   };
+  // interior stage: all 64 keys lie at or below every row of the wave, so there is no
+  // mask, no skipping and no ragged end.  Hand-scheduled: the 32 MFMAs go out in 8 groups
+  // of 4 (scores of half A, scores of half B, O update with A, O update with B); the LDS
+  // operands of group g+1 are fetched before the MFMAs of group g are issued, and between
+  // consecutive MFMAs sits a slice of VALU work that does not depend on them -- widening
+  // the next stage's K/V registers into LDS under the scores of A, the exponentials of A
+  // under the scores of B, the exponentials of B under the O update with A -- so the
+  // matrix pipe and the VALU of one wave run at the same time.
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)&lds[0][0];
+  const uint32_t kaddr0 = lds_base + (n < 16 ? 0 : RECB) + (half * 16 + (n & 15)) * 16;
+  const uint32_t vaddr0 = lds_base + 16 * HD * 2 + lane * 16;
+  // MFMAs of a stage in issue order: m in [0, NS): scores of A, k-step m; [NS, 2 NS): scores
+  // of B; then 2 NC O updates with A (32-row block c = idx/2, page idx%2 of the pair), then
+  // 2 NC with B.  Operands are fetched from LDS GS MFMAs ahead.
+  constexpr int GS = 2;
+  constexpr int NM = 2 * NS + 4 * NC, NG = NM / GS;
+  static_assert(NM % GS == 0 && NS % GS == 0 && (2 * NC) % GS == 0, "groups do not straddle phases");
+  auto stage_interior = [&](int st, int buf, bool do_store, bool do_load) {
+    const uint32_t ka = kaddr0 + buf * (4 * RECB), va = vaddr0 + buf * (4 * RECB);
+    hat_f16x8 op[2][GS];
+    f32x16 sA, sB;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f16x8 p0, p1;
+    float mx = 0.f, m_new = 0.f, ps = 0.f;
+    auto load_operand = [&](auto mc, hat_f16x8& dst) {
+      constexpr int m = decltype(mc)::value;
+      if constexpr (m < 2 * NS) {
+        constexpr int sub = m / NS, ks = m % NS;
+        dst = hat_lds_read<sub * 2 * RECB + ks * 512>(ka);
+      } else {
+        constexpr int idx = m - 2 * NS, sub = idx / (2 * NC), c = (idx % (2 * NC)) / 2, rec = idx % 2;
+        dst = hat_lds_read<(sub * 2 + rec) * RECB + c * 1024>(va);
+      }
+    };
+    // exponentials of elements [r0, r1) of a score tile, in place, and their sum
+    // (the empty asm statements keep the optimiser from sinking a slice's arithmetic down to
+    // where its results are used, which would undo the interleaving)
+    auto exps = [&](f32x16& sc, int r0, int r1) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (r >= r0 && r < r1) {
+          float e = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2, -m_new));
+          asm volatile("" : "+v"(e));
+          sc[r] = e;
+          ps += e;
+        }
+      asm volatile("" : "+v"(ps));
+    };
+    // softmax of one 32-key half in NSL slices: 0 = row maximum, 1 = exchange between the lane
+    // halves, the rest = exponentials
+    auto softmax_slice = [&](f32x16& sc, auto qc, auto nslc) {
+      constexpr int q = decltype(qc)::value, NSL = decltype(nslc)::value;
+      if constexpr (q == 0) {
+        mx = sc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+        asm volatile("" : "+v"(mx));
+      } else if constexpr (q == 1) {
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        m_new = fmaxf(m_run, mx * scale_log2);
+        asm volatile("" : "+v"(m_new));
+        ps = 0.f;
+      } else {
+        constexpr int parts = NSL - 2;
+        exps(sc, (q - 2) * 16 / parts, (q - 1) * 16 / parts);
+      }
+    };
+    auto rescale = [&]() {
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // wave-uniform: some row's maximum moved
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[c][r] *= alpha;
+        m_run = m_new;
+      }
+      l_run += ps;
+    };
+
+    if (do_load) load_page_ids(st + 2);  // consumed under the scores of B, half a stage from here
+    hat_static_for<GS>([&](auto jc) { load_operand(jc, op[0][decltype(jc)::value]); });
+    hat_static_for<NG>([&](auto gc) {
+      constexpr int G = decltype(gc)::value;
+      constexpr int cur = G & 1;
+      hat_wait_operands(op[cur]);
+      if constexpr (G + 1 < NG)
+        hat_static_for<GS>([&](auto jc) {
+          load_operand(std::integral_constant<int, (G + 1) * GS + decltype(jc)::value>{}, op[cur ^ 1][decltype(jc)::value]);
+        });
+      if constexpr (G * GS == 2 * NS) {              // scores of A are soft-maxed: pack them for the O update
+        rescale();
+        probs_to_f16(sA, p0, p1);
+      } else if constexpr (G * GS == 2 * NS + 2 * NC) {
+        rescale();
+        probs_to_f16(sB, p0, p1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      hat_static_for<GS>([&](auto jc) {
+        constexpr int j = decltype(jc)::value, m = G * GS + j;
+        if constexpr (m < NS) {                                  // scores of A | widen next stage into LDS
+          sA = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[cur][j], qreg[m], m == 0 ? zero16 : sA, 0, 0, 0);
+          if (do_store) *(u32x4*)(&lds[buf ^ 1][(m * 256 + threadIdx.x) * 16]) = kv_to_f16_bits(regs[m]);
+        } else if constexpr (m < 2 * NS) {                       // scores of B | loads of stage st+2, softmax of A
+          constexpr int q = m - NS;
+          sB = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[cur][j], qreg[q], q == 0 ? zero16 : sB, 0, 0, 0);
+          if (do_load) gload_one(std::integral_constant<int, q>{});
+          softmax_slice(sA, std::integral_constant<int, q>{}, std::integral_constant<int, NS>{});
+        } else if constexpr (m < 2 * NS + 2 * NC) {              // O update with A | softmax of B
+          constexpr int q = m - 2 * NS, c = q / 2;
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[cur][j], (q % 2) ? p1 : p0, o[c], 0, 0, 0);
+          softmax_slice(sB, std::integral_constant<int, q>{}, std::integral_constant<int, 2 * NC>{});
+        } else {                                                 // O update with B
+          constexpr int q = m - 2 * NS - 2 * NC, c = q / 2;
+          o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[cur][j], (q % 2) ? p1 : p0, o[c], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
+  };
 
   if (st0 < st1) {  // tiles are widened to fp16 once, on their way into LDS
-    gload(st0, regsA);
-    lstore(0, regsA);
+    gload(st0);
+    lstore(0);
+    if (st0 + 1 < st1) gload(st0 + 1);
   }
-  if (st0 + 1 < st1) gload(st0 + 1, regsB);
   __syncthreads();
 
-  for (int st = st0; st < st1; st += 2) {
-    // even step: LDS[0] holds stage st, regsB holds stage st+1, regsA is free
-    if (st + 2 < st1) gload(st + 2, regsA);
-    compute(st, 0);
-    if (st + 1 < st1) lstore(1, regsB);
+  // LDS[buf] holds stage st; the registers hold stage st+1, whose buffer everyone left at
+  // the barrier that ended stage st-1.  A wave's interior stages come first (two loops, so
+  // that each gets its own register allocation); every wave passes one barrier per stage.
+  int st_int = (wave_first_pos + 1) >> 6;
+  st_int = st_int < (kv_end >> 6) ? st_int : (kv_end >> 6);
+  if (!wave_live || st_int < st0) st_int = st0;
+  int st = st0;
+  for (; st < st_int; ++st) {
+    stage_interior(st, (st - st0) & 1, st + 1 < st1, st + 2 < st1);
     __syncthreads();
-    if (st + 1 >= st1) break;
-    // odd step: LDS[1] holds stage st+1, regsA holds stage st+2, regsB is free
-    if (st + 3 < st1) gload(st + 3, regsB);
-    compute(st + 1, 1);
-    if (st + 2 < st1) lstore(0, regsA);
+  }
+  for (; st < st1; ++st) {
+    const int buf = (st - st0) & 1;
+    if (st + 1 < st1) lstore(buf ^ 1);
+    if (st + 2 < st1) gload(st + 2);
+    compute(st, buf);
     __syncthreads();
   }
   l_run += __shfl_xor(l_run, 32);

@@ -27,9 +27,8 @@
 
 #include <algorithm>
 #include <cmath>
-#include <type_traits>
-#include <utility>
 
+#include "hat_device_util.h"
 #include "hat_kernels.h"
 #include "hat_layout.h"
 
@@ -44,36 +43,14 @@ __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)
 // fp32 -> fp16, round to nearest even, saturating instead of overflowing to infinity
 __device__ __forceinline__ _Float16 to_act(float x) { return (_Float16)__builtin_amdgcn_fmed3f(x, -65504.f, 65504.f); }
 
-// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
 template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
+__device__ __forceinline__ void static_for(F&& f) { hat_static_for<N>(f); }
 template <int OFF>
-__device__ __forceinline__ f16x8 lds_read(uint32_t addr) {
-  static_assert(OFF >= 0 && OFF < 65536, "ds_read offset field is 16 bits");
-  f16x8 v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
-  return v;
-}
+__device__ __forceinline__ f16x8 lds_read(uint32_t addr) { return hat_lds_read<OFF>(addr); }
 template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-// "operands have arrived": the wait is tied to the first register, the others are
-// threaded through empty asm statements (volatile asm keeps its order) so that no
-// MFMA using them can be scheduled above the wait.
+__device__ __forceinline__ void wait_vmcnt() { hat_wait_vmcnt<N>(); }
 template <int N>
-__device__ __forceinline__ void wait_operands(f16x8 (&v)[N]) {
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]));
-#pragma unroll
-  for (int i = 1; i < N; ++i) asm volatile("" : "+v"(v[i]));
-}
+__device__ __forceinline__ void wait_operands(f16x8 (&v)[N]) { hat_wait_operands(v); }
 
 template <int BF, int BT, int WF, int WT, int BKT, int NSTAGE>
 struct Tile {

@@ -197,6 +197,30 @@ def test_error_paths_are_atomic():
     p.check_pages(range(4))
     tok, ms = p.gpu.last_step_stats()
     assert tok == 52 and ms > 0
+    # the empty step: accepted, changes nothing (as in the page model)
+    snap = [p.gpu.kv_query(d) for d in range(4)]
+    assert p.gpu.forward([]) == [] and p.pages.step([]) == []
+    assert [p.gpu.kv_query(d) for d in range(4)] == snap
+    p.close()
+
+
+def test_limits_exactly_reached():
+    # a step of exactly max_step_tokens rows that ends exactly at max_pos; then the largest verify
+    # segment (8 rows) rolled back over a page boundary
+    p = Pair(hi.TINY, 62, n_pages=9, max_devices=2, max_step_tokens=128, max_pos=128)
+    outs, refs = p.step([(0, hi.CHUNK, 0, 128)])
+    check(outs, refs)
+    p.check_pages([0])
+    assert p.gpu.kv_query(0)[0] == 128 and len(p.gpu.kv_query(0)[1]) == 8
+    outs, refs = p.step([(0, hi.VERIFY, 120, 8)])            # rewrites the last 8 positions
+    check(outs, refs)
+    outs, refs = p.step([(0, hi.VERIFY, 111, 8)])            # back over the page boundary at 112
+    check(outs, refs)
+    p.check_pages([0])
+    assert p.gpu.kv_query(0)[0] == 119
+    outs, refs = p.step([(0, hi.VERIFY, 119, 1), (1, hi.CHUNK, 0, 1)])   # single rows
+    check(outs, refs)
+    p.check_pages([0, 1])
     p.close()
 
 
