@@ -61,7 +61,7 @@ Shapes make_shapes(const hat_mid_config_t& c) {
   s.Ngu = round_up(2 * s.Fpad, 256);
   s.Nd = round_up(s.d, 256);
   s.Tcap = round_up(c.max_step_tokens, 256);
-  s.attn_target = 512;
+  s.attn_target = 256;  // one 8-wave workgroup per CU
   s.verify_target = 2048;
   if (const char* e = getenv("HAT_ATTN_TARGET")) s.attn_target = s.verify_target = std::max(1, atoi(e));
   if (const char* e = getenv("HAT_VERIFY_TARGET")) s.verify_target = std::max(1, atoi(e));
@@ -69,7 +69,7 @@ Shapes make_shapes(const hat_mid_config_t& c) {
   s.chunk_items_cap = 2 * per_head + s.Tcap / 128 + c.max_devices + 2;
   s.verify_items_cap = 2 * per_head + c.max_devices + 2;
   s.merge_cap = s.Tcap / 16 + s.Tcap / 128 + 2 * c.max_devices + 2;
-  s.part_rows_cap = 128 * (2 * per_head + 2) + HAT_MAX_VERIFY * s.verify_items_cap;
+  s.part_rows_cap = HAT_CHUNK_QROWS * (2 * per_head + 2) + HAT_MAX_VERIFY * s.verify_items_cap;
   s.gemm_part_rows = 4096;
   s.plan_words = (size_t)3 * s.Tcap + 8 * ((size_t)s.Tcap / 16 + 2 * (size_t)c.max_devices + 2) + 8 * (size_t)c.max_devices + 16 + (size_t)c.n_pages + c.max_devices +
                  12 * ((size_t)s.chunk_items_cap + s.verify_items_cap) + 8 * (size_t)s.merge_cap + 64;
@@ -527,18 +527,28 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
         }
       }
     }
-    // chunk segments: 128-row tiles, optionally split along the keys
-    int base_tiles = 0;
-    for (int i = 0; i < S; ++i)
-      if (segs[i].kind == HAT_SEG_CHUNK) base_tiles += (segs[i].n + 127) / 128;
-    if (base_tiles) {
-      const int want = (base_tiles * s.H >= s.attn_target) ? 1 : (s.attn_target + base_tiles * s.H - 1) / (base_tiles * s.H);
+    // chunk segments: tiles of HAT_CHUNK_QROWS rows, split along the keys so that no work item
+    // is larger than a third of one workgroup slot's share of the launch (all heads do the same
+    // work, so a head has attn_target / H slots): the items, sorted by cost, then pack evenly.
+    double total_cost = 0;
+    for (int i = 0; i < S; ++i) {
+      if (segs[i].kind != HAT_SEG_CHUNK) continue;
+      for (int q0 = 0; q0 < segs[i].n; q0 += HAT_CHUNK_QROWS) {
+        const int nq = std::min(HAT_CHUNK_QROWS, segs[i].n - q0);
+        total_cost += (double)nq * (segs[i].start_pos + q0 + 0.5 * nq);
+      }
+    }
+    if (total_cost > 0) {
+      const double slots = std::max(1, s.attn_target / s.H);
+      const double cost_cap = std::max(256.0 * 256.0, total_cost / (3.0 * slots));
       for (int i = 0; i < S; ++i) {
         if (segs[i].kind != HAT_SEG_CHUNK) continue;
-        for (int q0 = 0; q0 < segs[i].n; q0 += 128) {
-          const int nq = std::min(128, segs[i].n - q0);
+        for (int q0 = 0; q0 < segs[i].n; q0 += HAT_CHUNK_QROWS) {
+          const int nq = std::min(HAT_CHUNK_QROWS, segs[i].n - q0);
           const int need = segs[i].start_pos + q0 + nq;
-          int ns = std::min(std::min(want, std::max(1, need / 256)), 16);
+          const double cost = (double)nq * (need - 0.5 * nq);
+          int ns = (int)std::ceil(cost / cost_cap);
+          ns = std::max(1, std::min(std::min(ns, std::max(1, need / 256)), 16));
           if ((int)citems.size() + ns > s.chunk_items_cap - 1 || part_row + ns * nq > s.part_rows_cap ||
               (int)mitems.size() + 9 >= s.merge_cap)
             ns = 1;

@@ -2,8 +2,8 @@
 //
 //   chunk  -- a prompt chunk of a device in the prefill phase (paper Sec. 2.1
 //             chunked prefill, Sec. 3.3): many query rows, matrix-core bound.
-//             One workgroup = 128 query rows (4 waves x 32) of one head; K/V tiles
-//             of 64 keys are staged in LDS and shared by the four waves.
+//             One workgroup = 256 query rows (8 waves x 32) of one head; K/V tiles
+//             of 64 keys are staged in LDS and shared by the eight waves.
 //   verify -- the draft sequence of a device in the decode phase verified in one
 //             step (Sec. 3.4): at most 8 query rows against a long cache, HBM
 //             bound.  One workgroup = one (segment, head, key range); each wave
@@ -294,12 +294,13 @@ __device__ __forceinline__ void probs_to_f16(const f32x16& pv, f16x8& p0, f16x8&
 }
 
 template <int HD>
-__global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAttn a) {
+__global__ __launch_bounds__(HAT_CHUNK_QROWS * 2) void attn_chunk_kernel(HatPlanDev p, HatAttn a) {
   constexpr int NS = HD / 16;
   constexpr int NC = HD / 32;
   constexpr int REC = 2 * 16 * HD;        // elements of one (page, head) record
   constexpr int RECB = REC * 2;           // bytes
-  constexpr int LPT = 4 * RECB / 16 / 256;  // 16-byte loads per thread per 64-key stage
+  constexpr int NTH = HAT_CHUNK_QROWS * 2;     // threads: one wave per 32 query rows
+  constexpr int LPT = 4 * RECB / 16 / NTH;     // 16-byte loads per thread per 64-key stage
   __shared__ __attribute__((aligned(1024))) unsigned char lds[2][4 * RECB];
 
   const HatAttnItem it = a.items[blockIdx.x];
@@ -345,8 +346,9 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
   // and are consumed one whole stage later.
   u32x4 regs[LPT];
   constexpr int UPR = RECB / 16;  // 16-byte units per (page, head) record
-  static_assert(LPT == NS && (256 % UPR == 0 || UPR % 256 == 0), "a thread's i-th unit lies in page (i*256)/UPR for every thread");
-  const uint32_t lane_off = threadIdx.x * 16;
+  static_assert(UPR % NTH == 0 || NTH == 2 * UPR, "a thread's i-th unit lies in a page that is the same for its whole wave");
+  const uint32_t lane_off = (UPR >= NTH ? threadIdx.x : threadIdx.x % UPR) * 16;
+  const int tsub = UPR >= NTH ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x / UPR);  // which of the two pages unit i spans
   int pgid[4];  // page ids of the stage to load next (the same for every thread)
   auto load_page_ids = [&](int st) {
 #pragma unroll
@@ -358,10 +360,19 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
   };
   auto gload_one = [&](auto ic) {
     constexpr int i = decltype(ic)::value;
-    constexpr int pg = (i * 256) / UPR, off0 = (i * 256) % UPR;  // same page for the whole workgroup
-    const int page = __builtin_amdgcn_readfirstlane(pgid[pg]);
+    int page;
+    uint32_t off;
+    if constexpr (UPR >= NTH) {  // the same page for the whole workgroup
+      constexpr int pg = (i * NTH) / UPR, off0 = (i * NTH) % UPR;
+      page = pgid[pg];
+      off = lane_off + off0 * 16;
+    } else {                     // the workgroup's i-th units span two pages, one per half
+      page = tsub ? pgid[2 * i + 1] : pgid[2 * i];
+      off = lane_off;
+    }
+    page = __builtin_amdgcn_readfirstlane(page);
     const unsigned char* rec = (const unsigned char*)pool + (size_t)page * RECB;  // wave-uniform
-    regs[i] = *(const u32x4*)(rec + lane_off + off0 * 16);
+    regs[i] = *(const u32x4*)(rec + off);
   };
   auto gload = [&](int st) {
     load_page_ids(st);
@@ -369,7 +380,7 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
   };
   auto lstore = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * 256 + threadIdx.x) * 16]) = kv_to_f16_bits(regs[i]);
+    for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * NTH + threadIdx.x) * 16]) = kv_to_f16_bits(regs[i]);
   };
   // general stage: causal masks, ragged ends, waves that skip a 32-key half
   auto compute = [&](int st, int buf) {
@@ -507,11 +518,15 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_kernel(HatPlanDev p, HatAtt
         constexpr int j = decltype(jc)::value, m = G * GS + j;
         if constexpr (m < NS) {                                  // scores of A | widen next stage into LDS
           sA = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[cur][j], qreg[m], m == 0 ? zero16 : sA, 0, 0, 0);
-          if (do_store) *(u32x4*)(&lds[buf ^ 1][(m * 256 + threadIdx.x) * 16]) = kv_to_f16_bits(regs[m]);
+          if constexpr (m < LPT) {
+            if (do_store) *(u32x4*)(&lds[buf ^ 1][(m * NTH + threadIdx.x) * 16]) = kv_to_f16_bits(regs[m]);
+          }
         } else if constexpr (m < 2 * NS) {                       // scores of B | loads of stage st+2, softmax of A
           constexpr int q = m - NS;
           sB = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[cur][j], qreg[q], q == 0 ? zero16 : sB, 0, 0, 0);
-          if (do_load) gload_one(std::integral_constant<int, q>{});
+          if constexpr (q < LPT) {
+            if (do_load) gload_one(std::integral_constant<int, q>{});
+          }
           softmax_slice(sA, std::integral_constant<int, q>{}, std::integral_constant<int, NS>{});
         } else if constexpr (m < 2 * NS + 2 * NC) {              // O update with A | softmax of B
           constexpr int q = m - 2 * NS, c = q / 2;
@@ -622,8 +637,8 @@ hipError_t hat_attn_init() { return hipSuccess; }
 hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStream_t st) {
   if (a.n_items <= 0) return hipSuccess;
   dim3 grid(a.n_items, a.H);
-  if (a.hd == 128) attn_chunk_kernel<128><<<grid, 256, 0, st>>>(p, a);
-  else if (a.hd == 64) attn_chunk_kernel<64><<<grid, 256, 0, st>>>(p, a);
+  if (a.hd == 128) attn_chunk_kernel<128><<<grid, HAT_CHUNK_QROWS * 2, 0, st>>>(p, a);
+  else if (a.hd == 64) attn_chunk_kernel<64><<<grid, HAT_CHUNK_QROWS * 2, 0, st>>>(p, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -9,6 +9,9 @@ typedef __bf16 bf16_t;    // storage type of the callers' weights, of hidden in/
 typedef _Float16 act_t;   // arithmetic type of the MFMA operands: re-tiled weights and all activations
 
 constexpr int HAT_MAX_VERIFY_ROWS = 8;  // query rows of a verify work item
+// query rows of one chunk-attention workgroup: 8 waves x 32 rows (the 64-key K/V stage that a
+// workgroup loads and widens is shared by all of them)
+constexpr int HAT_CHUNK_QROWS = 256;
 
 // ---- GEMM: out[t, f] = sum_k X[t, k] * W[f, k], operands in P32 layout ------
 enum HatEpilogue {
