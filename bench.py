@@ -15,7 +15,8 @@ Besides the contract line it reports, in the same JSON object:
   legs          chunk-attention MFMA fraction on a mixed-batch step and verify-
                 attention HBM GB/s on a verify-heavy step (30 devices)
   chunk_size_sweep  13B-shaped model, 8 devices x 8192-row prompts, chunk sizes 64..1024:
-                GPU time per step against chunk size and prefix (the cost profile g(.))
+                GPU time per step against chunk size and prefix (the cost profile g(.)), and the
+                chunk sizes the library's scheduler (Eq. 3) derives from it for a few uplinks
   cpu_baseline  the CPU oracle timed on this host on a bounded sample
   paper_context end-to-end numbers the paper reports on other hardware
 """
@@ -260,7 +261,32 @@ def chunk_sweep(n_layers, chunks=(64, 128, 256, 512, 1024), n_devices=8, prompt=
         log("sweep c=%d: %.2f ms/step mean (first %.2f, last %.2f), %.0f tokens/s" % (c, dt / steps * 1e3, ms[0], ms[2], n_devices * prompt / dt))
     m.close()
     return {"workload": "13B-shaped (%d layers, d 5120, 40x128 heads, FFN 13824), %d devices x %d-row prompts, "
-                        "all devices batched per step" % (n_layers, n_devices, prompt), "points": res}
+                        "all devices batched per step" % (n_layers, n_devices, prompt), "points": res,
+            "chunk_size_rule": chunk_size_rule(res, d)}
+
+
+def chunk_size_rule(points, d):
+    """The consumer of the sweep: the library's state monitor (hat_sched_*, Sec. 3.2) is fed the
+    measured (rows per step, ms per step) pairs and the chunk-size rule (Sec. 3.3, Eq. 3) is solved for
+    a few uplinks and pipeline lengths.  A = 2 d bytes per token (fp16 hidden state); the standing
+    load mu is the smallest measured batch (observed last, alpha = 0: the table is the sweep itself)."""
+    from paper_2503_18989_amd import HatSched
+    sched = HatSched([p["rows_per_step"] for p in points], alpha=0.0)
+    for p in sorted(points, key=lambda p: -p["rows_per_step"]):
+        sched.observe(p["rows_per_step"], p["ms_mean_step"])
+    A = 2.0 * d
+    rows = []
+    for mb_s in (1, 10, 100, 1000):
+        beta = mb_s * 1e6 / 1e3                       # bytes per ms
+        rows.append({"uplink_MB_per_s": mb_s,
+                     "chunk_size_P1": sched.chunk_size(A, beta, 1, 16, 8192),
+                     "chunk_size_P4": sched.chunk_size(A, beta, 4, 16, 8192),
+                     "parallel_draft_steps": sched.parallel_draft_steps(5, A, beta, 2 * beta, 20.0)})
+    out = {"mu_rows": sched.mu, "g_ms_at_mu": sched.predict(sched.mu), "bytes_per_token": A,
+           "note": "chunk sizes clamped to [16, 8192]; drafting delay 20 ms per step, downlink = 2 x uplink, draft length 5",
+           "by_uplink": rows}
+    sched.close()
+    return out
 
 
 # ---------------------------------------------------------------- measured HBM traffic (from profiles/)

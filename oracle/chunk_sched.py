@@ -21,6 +21,8 @@ and the reading taken here (the product takes the same readings):
      is at least (g(mu) + g(mu + X)) / P -- the first size at which the upload of the next chunk
      covers the in-cloud delay of this one (Eq. 3 holds with equality between X-1 and X);
      x_max if no size in the range does.
+ S5  The linear continuation of S1 can dip below zero far from the observed knots; lambda_i is a
+     number of inference steps, so the floor formula is clamped at 0.
 """
 import math
 
@@ -73,4 +75,4 @@ class ChunkSched:
     def parallel_draft_steps(self, draft_len, bytes_per_token, beta_up, beta_down, gamma):
         mu = 0.0 if self.mu is None else self.mu
         t = draft_len * bytes_per_token / beta_up + self.predict(mu) + draft_len * bytes_per_token / beta_down
-        return int(math.floor(t / gamma))
+        return max(0, int(math.floor(t / gamma)))   # a number of steps: not below zero (reading S5)

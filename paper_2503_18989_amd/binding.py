@@ -24,6 +24,8 @@ EXPORTED_SYMBOLS = [
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_import", "hat_mid_kv_export",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
     "hat_mid_debug_gemm_tile_count",
+    "hat_sched_create", "hat_sched_destroy", "hat_sched_observe", "hat_sched_mu", "hat_sched_predict",
+    "hat_sched_chunk_size", "hat_sched_parallel_draft_steps",
 ]
 
 
@@ -100,6 +102,21 @@ def load_library():
     lib.hat_mid_debug_force_gemm.argtypes = [vp, i32, i32, i32]
     lib.hat_mid_debug_gemm_tile_count.restype = i32
     lib.hat_mid_debug_gemm_tile_count.argtypes = []
+    f64 = C.c_double
+    lib.hat_sched_create.restype = i32
+    lib.hat_sched_create.argtypes = [C.POINTER(i32), i32, f64, C.POINTER(vp)]
+    lib.hat_sched_destroy.restype = None
+    lib.hat_sched_destroy.argtypes = [vp]
+    lib.hat_sched_observe.restype = i32
+    lib.hat_sched_observe.argtypes = [vp, f64, f64]
+    lib.hat_sched_mu.restype = f64
+    lib.hat_sched_mu.argtypes = [vp]
+    lib.hat_sched_predict.restype = f64
+    lib.hat_sched_predict.argtypes = [vp, f64]
+    lib.hat_sched_chunk_size.restype = i32
+    lib.hat_sched_chunk_size.argtypes = [vp, f64, f64, i32, i32, i32]
+    lib.hat_sched_parallel_draft_steps.restype = i32
+    lib.hat_sched_parallel_draft_steps.argtypes = [vp, f64, f64, f64, f64, f64]
     _LIB = lib
     return lib
 
@@ -236,6 +253,53 @@ class HatMid:
     def close(self):
         if getattr(self, "_handle", None) is not None and self._handle.value:
             self.lib.hat_mid_destroy(self._handle)
+            self._handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class HatSched:
+    """hat_sched_*: state monitor (Sec. 3.2) and chunk-size rule (Sec. 3.3) of the cloud.  Host code; needs no GPU."""
+
+    def __init__(self, knots, alpha=0.8):
+        self.lib = load_library()
+        arr = (C.c_int32 * len(knots))(*[int(k) for k in knots])
+        self._handle = C.c_void_p()
+        if self.lib.hat_sched_create(arr, len(knots), float(alpha), C.byref(self._handle)) != 0:
+            raise ValueError("hat_sched_create: invalid knots or alpha")
+
+    def observe(self, mu_hat, eta_hat):
+        if self.lib.hat_sched_observe(self._handle, float(mu_hat), float(eta_hat)) != 0:
+            raise ValueError("hat_sched_observe: invalid sample")
+
+    @property
+    def mu(self):
+        return self.lib.hat_sched_mu(self._handle)
+
+    def predict(self, tokens):
+        return self.lib.hat_sched_predict(self._handle, float(tokens))
+
+    def chunk_size(self, bytes_per_token, beta_up, pipeline_len, x_min, x_max):
+        x = self.lib.hat_sched_chunk_size(self._handle, float(bytes_per_token), float(beta_up), int(pipeline_len),
+                                          int(x_min), int(x_max))
+        if x < 0:
+            raise ValueError("hat_sched_chunk_size: invalid argument")
+        return x
+
+    def parallel_draft_steps(self, draft_len, bytes_per_token, beta_up, beta_down, gamma):
+        n = self.lib.hat_sched_parallel_draft_steps(self._handle, float(draft_len), float(bytes_per_token),
+                                                    float(beta_up), float(beta_down), float(gamma))
+        if n < 0:
+            raise ValueError("hat_sched_parallel_draft_steps: invalid argument")
+        return n
+
+    def close(self):
+        if getattr(self, "_handle", None) is not None and self._handle.value:
+            self.lib.hat_sched_destroy(self._handle)
             self._handle = C.c_void_p()
 
     def __del__(self):

@@ -9,14 +9,14 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhatmid.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "sched.cpp"]   # sched.cpp: host code only
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
          "-Wno-unused-result"]
 
 
 def _compile(src):
-    obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
+    obj = os.path.join(HERE, "_build", os.path.splitext(src)[0] + ".o")
     os.makedirs(os.path.dirname(obj), exist_ok=True)
     cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)

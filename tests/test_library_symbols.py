@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/hat_mid.h declares
+"""The C-ABI library loads and exports every symbol include/*.h declares
 (no compute: this runs without a GPU)."""
 import ctypes
 import os
@@ -10,9 +10,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    txt = open(os.path.join(ROOT, "include", "hat_mid.h")).read()
-    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
-    return sorted(set(re.findall(r"\b(hat_mid_\w+)\s*\(", txt)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        txt = open(os.path.join(ROOT, "include", header)).read()
+        txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+        names |= set(re.findall(r"\b(hat_(?:mid|sched)_\w+)\s*\(", txt))
+    return sorted(names)
 
 
 def test_header_declares_the_three_named_calls():

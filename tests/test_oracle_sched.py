@@ -94,3 +94,7 @@ def test_parallel_draft_steps_is_the_floor_formula():
     assert s.parallel_draft_steps(5, 8192.0, 1e3, 2e3, 7.0) == 14
     assert s.parallel_draft_steps(5, 8192.0, 1e3, 2e3, 101.44) == 1
     assert s.parallel_draft_steps(5, 8192.0, 1e3, 2e3, 101.45) == 0
+    # a table whose continuation is negative at mu: the count stays at 0
+    s2 = ChunkSched([100, 200], 0.0)
+    s2.observe(100, 1.0); s2.observe(200, 50.0); s2.observe(1, 0.0)   # the last sample moves mu to 1 and the knot at 100 to 0
+    assert s2.predict(s2.mu) < 0 and s2.parallel_draft_steps(0, 8192.0, 1e3, 2e3, 5.0) == 0
