@@ -18,6 +18,12 @@
  * sub-block.  A row at absolute position p attends to keys 0..p of its own
  * device only.
  *
+ * Arithmetic: weights and the KV cache hold bf16 values; matrix products take
+ * fp16 operands (activations are produced in fp16, saturating; bf16 weights and
+ * cache rows are widened to fp16, exact for magnitudes in [2^-17, 65504]) and
+ * accumulate in fp32; softmax, normalisation, rotary embedding, SiLU and the
+ * residual stream are fp32.
+ *
  * Conventions
  *  - "device pointer" = address in GPU memory (HBM) of the current HIP device;
  *    "host pointer" = ordinary process memory.  Every struct is read during the

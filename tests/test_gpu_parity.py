@@ -1,7 +1,7 @@
 """GPU parity: the HIP library against the CPU oracle on the same seeded inputs.
 
-Bar: max|gpu - ref| / max|ref| <= 2e-2 per segment on output hidden states (bf16
-operands, fp32 accumulation, fp32 residual stream); page ids, slots and cache
+Bar: max|gpu - ref| / max|ref| <= 2e-2 per segment on output hidden states (bf16-valued
+weights and cache, fp16 MFMA operands, fp32 accumulation, fp32 residual stream); page ids, slots and cache
 lengths bit-exact against the integer page model."""
 import os
 
