@@ -18,6 +18,7 @@ Besides the contract line it reports, in the same JSON object:
                 GPU time per step against chunk size and prefix (the cost profile g(.)), and the
                 chunk sizes the library's scheduler (Eq. 3) derives from it for a few uplinks
   cpu_baseline  the CPU oracle timed on this host on a bounded sample
+  host_fed      the same workload with hidden states in pinned host memory (PCIe-inclusive; not the metric)
   paper_context end-to-end numbers the paper reports on other hardware
 """
 from __future__ import annotations
@@ -131,6 +132,41 @@ def run_cfg2(m, arrs, steps, warmup):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     return wall, e0.elapsed_time(e1) / 1e3
+
+
+def run_cfg2_host(m, cfg, steps, warmup, n_chunks=8, chunk=256):
+    """The same cfg-2 step fed from pinned host memory through hat_mid_forward_host (upload of the next
+    chunk overlaps the current step; results copied back to host): the PCIe-inclusive rate."""
+    import torch
+    from paper_2503_18989_amd.binding import CSegment
+    stream = torch.cuda.current_stream()
+    sp = C.c_void_p(stream.cuda_stream)
+    xs, outs, arrs = [], [], []
+    for i in range(n_chunks):
+        x = torch.from_numpy(hi.bf16_bits(hi.hidden_rows(chunk, cfg["d_model"], SEED, i)).view(np.int16)).view(torch.bfloat16).pin_memory()
+        o = torch.empty_like(x).pin_memory()
+        arr = (CSegment * 1)()
+        arr[0] = CSegment(0, hi.CHUNK, chunk, i * chunk, x.data_ptr(), o.data_ptr())
+        xs.append(x); outs.append(o); arrs.append(arr)
+
+    def one(i):
+        j = i % n_chunks
+        if j == 0:
+            m.release(0)
+        rc = m.lib.hat_mid_forward_host(m._handle, arrs[j], 1, sp)
+        if rc != 0:
+            m._check(rc)
+    for i in range(warmup):
+        one(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(warmup, warmup + steps):
+        one(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return {"value": chunk * steps / wall, "unit": "hidden tokens/s", "ms_per_step": wall / steps * 1e3,
+            "bytes_per_step_each_way": chunk * cfg["d_model"] * 2,
+            "note": "hidden states start and end in pinned host memory (hat_mid_forward_host); never the headline value"}
 
 
 def profile_classes(m, run_steps):
@@ -358,6 +394,8 @@ def main():
     T = 256
     value = T * a.steps / sec
     log("cfg2: %.3f ms/step, %.0f hidden tokens/s" % (sec / a.steps * 1e3, value))
+    host_fed = run_cfg2_host(m, cfg, a.steps, a.warmup)
+    log("cfg2 from host memory: %.3f ms/step, %.0f hidden tokens/s" % (host_fed["ms_per_step"], host_fed["value"]))
 
     # per-class timing (separate pass, events around every launch)
     def cyc():
@@ -424,6 +462,7 @@ def main():
         "gpu_event_ms_per_step": gpu_s / a.steps * 1e3, "host_wall_ms_per_step": wall / a.steps * 1e3,
         "step_roofline_ms": ideal * 1e3, "step_roofline_frac": ideal / (sec / a.steps),
         "roofline": roofline, "kernels": kernels, "legs": legs, "chunk_size_sweep": sweep, "cpu_baseline": cpu,
+        "host_fed": host_fed,
         "paper_context": "paper reports end-to-end TTFT -41..54% / TBT -41..77% on 30 Jetson devices + 8xA6000 "
                          "(other hardware, whole system): context only, not a target",
     }

@@ -134,6 +134,19 @@ hat_status_t hat_mid_create(const hat_mid_config_t* cfg, const hat_mid_layer_wei
  * HAT_OK, nothing is enqueued and no state changes (segs may be NULL then). */
 hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream);
 
+/* The same step for hidden states that live in HOST memory (the form in which they
+ * arrive from the devices; Sec. 3.3: the transfer of one chunk overlaps the
+ * processing of another).  hidden_in / hidden_out of every segment are host
+ * pointers here, read and written asynchronously: keep them alive and untouched
+ * until hip_stream has been synchronised.  The rows are uploaded on a stream of
+ * the library's own into one of two staging slots in the workspace, the step
+ * runs on hip_stream once they have arrived, and the results are copied back
+ * on hip_stream; the upload of the next call therefore overlaps the
+ * computation of this one.  Overlap needs pinned memory (hipHostMalloc); with
+ * pageable memory the copies are still correct but serialise.  Validation,
+ * errors and atomicity are those of hat_mid_forward. */
+hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream);
+
 /* The device left (Sec. 2.1: requests leave the batch): all its pages return to
  * the pool, its length becomes 0.  Unknown-but-valid ids are a no-op. */
 hat_status_t hat_mid_release(hat_mid_t* h, int32_t device_id);

@@ -20,7 +20,7 @@ KERNEL_NAMES = ["gather", "rmsnorm", "gemm_qkv", "rope_append", "attn_chunk", "a
                 "gemm_o", "gemm_gateup", "gemm_down", "scatter"]
 DUMP_IDS = {"xnorm": 0, "q": 1, "attn": 2, "xnorm2": 3, "act": 4}
 EXPORTED_SYMBOLS = [
-    "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_release",
+    "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_forward_host", "hat_mid_release",
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_import", "hat_mid_kv_export",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
     "hat_mid_debug_gemm_tile_count",
@@ -78,6 +78,8 @@ def load_library():
     lib.hat_mid_create.argtypes = [C.POINTER(Config), C.POINTER(LayerWeights), vp, vp, vp, C.POINTER(vp)]
     lib.hat_mid_forward.restype = i32
     lib.hat_mid_forward.argtypes = [vp, C.POINTER(CSegment), i32, vp]
+    lib.hat_mid_forward_host.restype = i32
+    lib.hat_mid_forward_host.argtypes = [vp, C.POINTER(CSegment), i32, vp]
     lib.hat_mid_release.restype = i32
     lib.hat_mid_release.argtypes = [vp, i32]
     lib.hat_mid_destroy.restype = None
@@ -192,6 +194,24 @@ class HatMid:
             outs.append(out)
             arr[i] = CSegment(s.device_id, s.kind, x.shape[0], s.start_pos, x.data_ptr(), out.data_ptr())
         self._check(self.lib.hat_mid_forward(self._handle, arr, n, self._stream(stream)))
+        return outs
+
+    def forward_host(self, segments, stream=None):
+        """segments: list of Segment whose hidden_in (and hidden_out, if given) are CPU tensors, pinned for
+        overlap.  Returns the list of output CPU tensors, valid once the stream has been synchronised."""
+        torch = self.torch
+        n = len(segments)
+        arr = (CSegment * max(n, 1))()
+        outs = []
+        for i, s in enumerate(segments):
+            x = s.hidden_in
+            assert (not x.is_cuda) and x.dtype == self.io_torch and x.is_contiguous() and x.shape[1] == self.d
+            out = s.hidden_out if s.hidden_out is not None else torch.empty_like(x, pin_memory=x.is_pinned())
+            assert not out.is_cuda and out.is_contiguous()
+            outs.append(out)
+            arr[i] = CSegment(s.device_id, s.kind, x.shape[0], s.start_pos, x.data_ptr(), out.data_ptr())
+        self._keep_host = (segments, outs)   # the copies are asynchronous
+        self._check(self.lib.hat_mid_forward_host(self._handle, arr, n, self._stream(stream)))
         return outs
 
     def forward_raw(self, arr, n, stream_ptr):

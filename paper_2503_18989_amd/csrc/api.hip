@@ -101,6 +101,8 @@ struct Buffers {
   float* gemm_part;
   int32_t* plan_dev;
   int32_t* fixture_pages;
+  float* stage_in[2];
+  float* stage_out;
 };
 
 size_t carve(const hat_mid_config_t& c, const Shapes& s, void* base, Buffers* out) {
@@ -128,6 +130,11 @@ size_t carve(const hat_mid_config_t& c, const Shapes& s, void* base, Buffers* ou
   b.gemm_part = cv.take<float>((size_t)s.gemm_part_rows * s.d);
   b.plan_dev = cv.take<int32_t>(s.plan_words);
   b.fixture_pages = cv.take<int32_t>((size_t)(c.max_pos + 15) / 16 + 2);
+  // staging for steps whose hidden states live in host memory: two input slots (the upload of the
+  // next step overlaps the current one) and one output slot, sized for fp32 rows
+  b.stage_in[0] = cv.take<float>((size_t)s.Tcap * s.d);
+  b.stage_in[1] = cv.take<float>((size_t)s.Tcap * s.d);
+  b.stage_out = cv.take<float>((size_t)s.Tcap * s.d);
   if (out) *out = b;
   return align_up(cv.off, 256);
 }
@@ -164,6 +171,12 @@ struct hat_mid {
   struct Rec { int id; hipEvent_t a, b; };
   std::vector<Rec> recs;
   std::vector<hipEvent_t> ev_pool;
+
+  // steps fed from host memory (hat_mid_forward_host)
+  hipStream_t copy_stream = nullptr;
+  hipEvent_t up_done[2] = {nullptr, nullptr}, slot_free[2] = {nullptr, nullptr};
+  bool slot_used[2] = {false, false};
+  int host_slot = 0;
 
   int force_tile[4] = {-1, -1, -1, -1};   // tuning overrides per GEMM class (qkv, o, gate/up, down)
   int force_ksplit[4] = {0, 0, 0, 0};
@@ -287,6 +300,11 @@ hat_status_t hat_mid_create(const hat_mid_config_t* cfg, const hat_mid_layer_wei
       return bail(e, "pinned plan buffer");
     if ((e = hipEventCreateWithFlags(&h->plan_ev[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
   }
+  if ((e = hipStreamCreateWithFlags(&h->copy_stream, hipStreamNonBlocking)) != hipSuccess) return bail(e, "copy stream");
+  for (int i = 0; i < 2; ++i) {
+    if ((e = hipEventCreateWithFlags(&h->up_done[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+    if ((e = hipEventCreateWithFlags(&h->slot_free[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+  }
   if ((e = hipEventCreate(&h->ev_begin)) != hipSuccess) return bail(e, "event");
   if ((e = hipEventCreate(&h->ev_end)) != hipSuccess) return bail(e, "event");
 
@@ -334,6 +352,11 @@ void hat_mid_destroy(hat_mid_t* h) {
   }
   if (h->ev_begin) (void)hipEventDestroy(h->ev_begin);
   if (h->ev_end) (void)hipEventDestroy(h->ev_end);
+  for (int i = 0; i < 2; ++i) {
+    if (h->up_done[i]) (void)hipEventDestroy(h->up_done[i]);
+    if (h->slot_free[i]) (void)hipEventDestroy(h->slot_free[i]);
+  }
+  if (h->copy_stream) (void)hipStreamDestroy(h->copy_stream);
   for (auto& r : h->recs) {
     (void)hipEventDestroy(r.a);
     (void)hipEventDestroy(r.b);
@@ -701,6 +724,51 @@ static hat_status_t fixture_pages(hat_mid_t* h, const DeviceState& d, int pos0, 
   HIP_TRY(h, hipStreamSynchronize(st));  // the staging area below is reused by every fixture call
   HIP_TRY(h, hipMemcpy(h->b.fixture_pages, d.pages.data() + p0, (size_t)(p1 - p0 + 1) * sizeof(int32_t),
                        hipMemcpyHostToDevice));
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
+  if (!h) return HAT_EINVAL;
+  if (n_segs == 0) return HAT_OK;
+  if (!segs || n_segs < 0) return fail(h, HAT_EINVAL, "no segments");
+  if (n_segs > h->cfg.max_devices) return fail(h, HAT_EINVAL, "more segments (%d) than devices", n_segs);
+  const Shapes& s = h->s;
+  const size_t rowb = (size_t)s.d * (h->cfg.io_dtype == HAT_F32 ? 4 : 2);
+  long total = 0;
+  for (int i = 0; i < n_segs; ++i) {
+    if (segs[i].n <= 0 || !segs[i].hidden_in || !segs[i].hidden_out)
+      return fail(h, HAT_EINVAL, "segment %d: n = %d or a null host pointer", i, segs[i].n);
+    total += segs[i].n;
+  }
+  if (total > s.Tcap) return fail(h, HAT_EINVAL, "step of %ld rows exceeds max_step_tokens %d", total, s.Tcap);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int slot = h->host_slot;
+  h->host_slot ^= 1;
+  // this input slot was last read by the step two calls back
+  if (h->slot_used[slot]) HIP_TRY(h, hipStreamWaitEvent(h->copy_stream, h->slot_free[slot], 0));
+  std::vector<hat_mid_segment_t> dsegs(segs, segs + n_segs);
+  unsigned char* in = (unsigned char*)h->b.stage_in[slot];
+  unsigned char* out = (unsigned char*)h->b.stage_out;
+  size_t off = 0;
+  for (int i = 0; i < n_segs; ++i) {
+    const size_t nb = (size_t)segs[i].n * rowb;
+    HIP_TRY(h, hipMemcpyAsync(in + off, segs[i].hidden_in, nb, hipMemcpyHostToDevice, h->copy_stream));
+    dsegs[i].hidden_in = in + off;
+    dsegs[i].hidden_out = out + off;
+    off += nb;
+  }
+  HIP_TRY(h, hipEventRecord(h->up_done[slot], h->copy_stream));
+  HIP_TRY(h, hipStreamWaitEvent(st, h->up_done[slot], 0));
+  const hat_status_t rc = hat_mid_forward(h, dsegs.data(), n_segs, hip_stream);
+  HIP_TRY(h, hipEventRecord(h->slot_free[slot], st));
+  h->slot_used[slot] = true;
+  if (rc != HAT_OK) return rc;
+  off = 0;
+  for (int i = 0; i < n_segs; ++i) {
+    const size_t nb = (size_t)segs[i].n * rowb;
+    HIP_TRY(h, hipMemcpyAsync(segs[i].hidden_out, out + off, nb, hipMemcpyDeviceToHost, st));
+    off += nb;
+  }
   return HAT_OK;
 }
 

@@ -236,3 +236,43 @@ def test_profiling_counts_every_kernel_class():
     assert all(ms >= 0 for ms, _ in t.values())
     p.gpu.set_profiling(False)
     p.close()
+
+
+@pytest.mark.parametrize("pinned", [True, False], ids=["pinned", "pageable"])
+def test_host_fed_steps_equal_device_fed_steps(pinned):
+    # hat_mid_forward_host (upload on the library's copy stream into alternating staging slots, results
+    # copied back on the compute stream) must give bit-identical rows and the same page tables as
+    # hat_mid_forward on device buffers; several steps are enqueued back to back before the first sync
+    import torch
+    from gpu_util import dev_weights
+    from paper_2503_18989_amd import HatMid, Segment
+    cfg = SMALL128
+    ws = [hi.layer_weights(cfg, l, 81, gain_jitter=0.1) for l in range(cfg["n_layers"])]
+    kw = dict(n_pages=64, max_devices=4, max_step_tokens=512, max_pos=1024)
+    a = HatMid(cfg, [dev_weights(w) for w in ws], **kw)
+    b = HatMid(cfg, [dev_weights(w) for w in ws], **kw)
+    steps = [[(0, hi.CHUNK, 0, 200), (1, hi.CHUNK, 0, 33)],
+             [(0, hi.CHUNK, 200, 130), (1, hi.VERIFY, 33, 5), (2, hi.CHUNK, 0, 64)],
+             [(0, hi.VERIFY, 330, 8), (1, hi.VERIFY, 35, 4), (2, hi.VERIFY, 64, 1)],
+             [(2, hi.CHUNK, 60, 300), (0, hi.VERIFY, 333, 5)]]
+    host_in, host_out, dev_out = [], [], []
+    for k, segs in enumerate(steps):
+        xs = [hi.hidden_rows(n, cfg["d_model"], 81, k, d) for d, _, _, n in segs]
+        cpu = [torch.from_numpy(hi.bf16_bits(x).view(np.int16)).view(torch.bfloat16) for x in xs]
+        if pinned:
+            cpu = [t.pin_memory() for t in cpu]
+        host_in.append(cpu)
+        host_out.append(b.forward_host([Segment(d, kind, st, t) for (d, kind, st, n), t in zip(segs, cpu)]))
+        dev_out.append(a.forward([Segment(d, kind, st, t.cuda()) for (d, kind, st, n), t in zip(segs, cpu)]))
+    torch.cuda.synchronize()
+    for ho, do in zip(host_out, dev_out):
+        for x, y in zip(ho, do):
+            assert torch.equal(x.view(torch.int16), y.cpu().view(torch.int16))
+    for d in range(4):
+        assert a.kv_query(d) == b.kv_query(d)
+    # an invalid step leaves the state alone on this path too
+    from paper_2503_18989_amd import HatError
+    with pytest.raises(HatError):
+        b.forward_host([Segment(0, hi.CHUNK, 999, host_in[0][0])])
+    assert a.kv_query(0) == b.kv_query(0)
+    a.close(); b.close()
