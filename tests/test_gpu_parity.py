@@ -276,3 +276,44 @@ def test_host_fed_steps_equal_device_fed_steps(pinned):
         b.forward_host([Segment(0, hi.CHUNK, 999, host_in[0][0])])
     assert a.kv_query(0) == b.kv_query(0)
     a.close(); b.close()
+
+
+@pytest.mark.parametrize("cfg,seed", [(SMALL128, 5), (SMALL64, 6)], ids=["hd128", "hd64"])
+def test_randomized_schedules(cfg, seed):
+    # seeded random mixes of chunks (1..600 rows), verify segments (1..8 rows, with rollback of 0..4
+    # rows first), departures and re-joins over 6 devices: every step against the oracle, page tables
+    # against the page model
+    rng = np.random.default_rng(seed)
+    ndev, max_pos, max_step = 6, 2048, 1024
+    p = Pair(cfg, 90 + seed, n_pages=6 * 2048 // 16 + 8, max_devices=ndev, max_step_tokens=max_step, max_pos=max_pos)
+    ln = [0] * ndev
+    for step in range(36):
+        segs, rows = [], 0
+        for d in rng.permutation(ndev):
+            d = int(d)
+            r = rng.random()
+            if r < 0.25:
+                continue
+            if r < 0.32 and ln[d] > 0:
+                p.gpu.release(d); p.ref.release(d); p.pages.release(d)
+                ln[d] = 0
+                continue
+            if ln[d] == 0 or r < 0.65:
+                n = int(rng.choice([1, 7, 16, 33, 64, 100, 129, 255, 256, 257, 400, 600]))
+                n = min(n, max_pos - ln[d], max_step - rows)
+                if n <= 0:
+                    continue
+                segs.append((d, hi.CHUNK, ln[d], n)); ln[d] += n
+            else:
+                back = int(min(rng.integers(0, 5), ln[d]))
+                n = int(min(rng.integers(1, 9), max_pos - (ln[d] - back), max_step - rows))
+                if n <= 0:
+                    continue
+                segs.append((d, hi.VERIFY, ln[d] - back, n)); ln[d] = ln[d] - back + n
+            rows += segs[-1][3]
+        if not segs:
+            continue
+        outs, refs = p.step(segs)
+        check(outs, refs)
+        p.check_pages(range(ndev))
+    p.close()
