@@ -233,6 +233,14 @@ hat_status_t hat_mid_debug_dump(hat_mid_t* h, int32_t which, void* dst, void* hi
  * beyond fp32 summation order. */
 hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile, int32_t ksplit);
 
+/* The automatic choice for a GEMM of T rows: Nw = weight rows (padded to 256), Nout = logical
+ * output features, K = inner dimension (multiple of 64), epilogue 0 = fp16 output, 1 = SwiGLU,
+ * 2 = accumulate into the residual (the only one whose K may be split; part_rows = capacity of
+ * the partial-sum buffer in rows, 0 = no buffer).  Host code only, no GPU work; for tests of the
+ * planner.  Returns HAT_EINVAL on a null pointer. */
+hat_status_t hat_mid_debug_gemm_plan(int32_t T, int32_t Nw, int32_t Nout, int32_t K, int32_t epilogue,
+                                     int32_t part_rows, int32_t* tile, int32_t* ksplit);
+
 /* Number of entries in the library's GEMM tile table (valid `tile` values of
  * hat_mid_debug_force_gemm are 0 .. count-1).  No GPU work. */
 int32_t hat_mid_debug_gemm_tile_count(void);

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_forward_host", "hat_mid_release",
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_import", "hat_mid_kv_export",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
-    "hat_mid_debug_gemm_tile_count",
+    "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_plan",
     "hat_sched_create", "hat_sched_destroy", "hat_sched_observe", "hat_sched_mu", "hat_sched_predict",
     "hat_sched_chunk_size", "hat_sched_parallel_draft_steps",
 ]
@@ -104,6 +104,8 @@ def load_library():
     lib.hat_mid_debug_force_gemm.argtypes = [vp, i32, i32, i32]
     lib.hat_mid_debug_gemm_tile_count.restype = i32
     lib.hat_mid_debug_gemm_tile_count.argtypes = []
+    lib.hat_mid_debug_gemm_plan.restype = i32
+    lib.hat_mid_debug_gemm_plan.argtypes = [i32, i32, i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     f64 = C.c_double
     lib.hat_sched_create.restype = i32
     lib.hat_sched_create.argtypes = [C.POINTER(i32), i32, f64, C.POINTER(vp)]

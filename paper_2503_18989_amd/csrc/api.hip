@@ -819,6 +819,21 @@ hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile,
 
 int32_t hat_mid_debug_gemm_tile_count(void) { return hat_gemm_tile_count(); }
 
+hat_status_t hat_mid_debug_gemm_plan(int32_t T, int32_t Nw, int32_t Nout, int32_t K, int32_t epilogue,
+                                     int32_t part_rows, int32_t* tile, int32_t* ksplit) {
+  if (!tile || !ksplit) return HAT_EINVAL;
+  HatGemm g{};
+  static float dummy;   // only its non-nullness is looked at
+  g.T = T; g.Nw = Nw; g.Nout = Nout; g.K = K; g.epilogue = epilogue;
+  g.part = part_rows > 0 ? &dummy : nullptr;
+  g.part_rows = part_rows;
+  g.force_tile = -1;
+  const HatGemmPlan p = hat_gemm_plan(g);
+  *tile = p.tile;
+  *ksplit = p.ksplit;
+  return HAT_OK;
+}
+
 hat_status_t hat_mid_debug_dump(hat_mid_t* h, int32_t which, void* dst, void* hip_stream) {
   if (!h || !dst) return HAT_EINVAL;
   if (!h->have_step) return fail(h, HAT_EINVAL, "no step has run yet");
