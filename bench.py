@@ -14,9 +14,10 @@ Besides the contract line it reports, in the same JSON object:
   kernels       every kernel class of the step: average duration and roofline
   legs          chunk-attention MFMA fraction on a mixed-batch step and verify-
                 attention HBM GB/s on a verify-heavy step (30 devices)
-  chunk_size_sweep  13B-shaped model, 8 devices x 8192-row prompts, chunk sizes 64..1024:
-                GPU time per step against chunk size and prefix (the cost profile g(.)), and the
-                chunk sizes the library's scheduler (Eq. 3) derives from it for a few uplinks
+  chunk_size_sweep  13B-shaped model, 8192-row prompts, chunk sizes 64..1024, with the 8 devices batched
+                per step and with one device per step: GPU time per step against chunk size and prefix
+                (the cost profile g(.)), chunk-attention MFMA / min-roofline fraction per chunk size,
+                and the chunk sizes the library's scheduler (Eq. 3) derives for a few uplinks
   cpu_baseline  the CPU oracle timed on this host on a bounded sample
   host_fed      the same workload with hidden states in pinned host memory (PCIe-inclusive; not the metric)
   paper_context end-to-end numbers the paper reports on other hardware
@@ -274,30 +275,53 @@ def chunk_sweep(n_layers, chunks=(64, 128, 256, 512, 1024), n_devices=8, prompt=
     sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
     x = to_dev_bf16(hi.hidden_rows(max(chunks), d, SEED + 5, 0))      # the same rows for every device and step
     out = torch.empty((n_devices, max(chunks), d), dtype=torch.bfloat16, device="cuda")
-    res = []
-    for c in chunks:
+    def feed(c, ndev):
+        """All chunks of size c of `ndev` prompts, one step per chunk position; returns the sweep point."""
         for dev in range(n_devices):
             m.release(dev)
         steps = prompt // c
-        arr = (CSegment * n_devices)()
-        ms = []
+        arr = (CSegment * ndev)()
+        ms, attn = [], None
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        extra = 0.0
         for j in range(steps):
-            for dev in range(n_devices):
+            for dev in range(ndev):
                 arr[dev] = CSegment(dev, hi.CHUNK, c, j * c, x.data_ptr(), out[dev].data_ptr())
-            m.forward_raw(arr, n_devices, sp)
+            if j == steps // 2:            # the middle step again under per-kernel events: attention figures
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                m.set_profiling(True); m.kernel_times()
+                m.forward_raw(arr, ndev, sp)
+                torch.cuda.synchronize()
+                kt = m.kernel_times(); m.set_profiling(False)
+                for dev in range(ndev):    # undo: the timed step below appends the same rows again
+                    arr[dev] = CSegment(dev, hi.CHUNK, c, j * c, x.data_ptr(), out[dev].data_ptr())
+                sec_a = kt["attn_chunk"][0] / max(kt["attn_chunk"][1], 1) / 1e3
+                fl, by = attn_work([(j * c, c)] * ndev, d)
+                attn = {"us_per_launch": sec_a * 1e6, "mfma_frac": fl / sec_a / PEAK_MFMA_BF16,
+                        "min_roofline_frac": max(fl / PEAK_MFMA_BF16, by / PEAK_HBM) / sec_a, "prefix": j * c}
+                extra += time.perf_counter() - t1
+            m.forward_raw(arr, ndev, sp)
             if j in (0, steps // 2, steps - 1):
                 ms.append(m.last_step_stats()[1])
         torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        res.append({"chunk": c, "rows_per_step": n_devices * c, "steps": steps, "ms_first_step": ms[0],
-                    "ms_middle_step": ms[1], "ms_last_step": ms[2], "ms_mean_step": dt / steps * 1e3,
-                    "hidden_tokens_per_s": n_devices * prompt / dt})
-        log("sweep c=%d: %.2f ms/step mean (first %.2f, last %.2f), %.0f tokens/s" % (c, dt / steps * 1e3, ms[0], ms[2], n_devices * prompt / dt))
+        dt = time.perf_counter() - t0 - extra
+        return {"chunk": c, "rows_per_step": ndev * c, "steps": steps, "ms_first_step": ms[0],
+                "ms_middle_step": ms[1], "ms_last_step": ms[2], "ms_mean_step": dt / steps * 1e3,
+                "hidden_tokens_per_s": ndev * prompt / dt, "chunk_attention_middle_step": attn}
+
+    res, res1 = [], []
+    for c in chunks:
+        res.append(feed(c, n_devices))
+        log("sweep c=%d: %.2f ms/step mean (first %.2f, last %.2f), %.0f tokens/s" % (c, res[-1]["ms_mean_step"], res[-1]["ms_first_step"], res[-1]["ms_last_step"], res[-1]["hidden_tokens_per_s"]))
+    for c in chunks:
+        res1.append(feed(c, 1))
+        log("sweep c=%d, one device per step: %.2f ms/step mean, %.0f tokens/s" % (c, res1[-1]["ms_mean_step"], res1[-1]["hidden_tokens_per_s"]))
     m.close()
     return {"workload": "13B-shaped (%d layers, d 5120, 40x128 heads, FFN 13824), %d devices x %d-row prompts, "
                         "all devices batched per step" % (n_layers, n_devices, prompt), "points": res,
+            "points_one_device_per_step": res1,
             "chunk_size_rule": chunk_size_rule(res, d)}
 
 
