@@ -164,6 +164,34 @@ def verify_schedule(seed, lengths, steps=64, k=5, rollback=True):
     return out
 
 
+def random_tree(seed, n, *key):
+    """A seeded forest of n candidate nodes in parents-first order (the shape of a
+    tree-verification step, paper Sec. 2.2; size 8 in Sec. 4.1): parents[i] in
+    {-1 (hangs off the last committed token), 0 .. i-1}."""
+    r = _rng(seed, 23, n, *key)
+    return [-1] + [int(r.integers(-1, i)) for i in range(1, n)]
+
+
+def tree_masks(parents):
+    """parents -> per-node bit masks (bit j: node j is the node itself or an ancestor)."""
+    masks = []
+    for i, p in enumerate(parents):
+        masks.append((1 << i) | (masks[p] if p >= 0 else 0))
+    return masks
+
+
+def tree_path(parents, node):
+    """Indices from the root down to `node`."""
+    path = []
+    while node >= 0:
+        path.append(node)
+        node = parents[node]
+    return path[::-1]
+
+
+MEDUSA_LIKE_TREE = [-1, 0, 0, 1, 1, 2, 3, -1]   # a fixed 8-node shape: two first candidates, branching below
+
+
 def sweep_schedule(chunk, prompt=8192, n_devices=8, batched=True):
     """Config 5: n_devices prompts of `prompt` rows fed in chunks of `chunk`;
     batched: all devices submit their j-th chunk in the same step."""

@@ -22,10 +22,25 @@ values the harness generated, widened); `dtype=np.float32` gives the fp32
 variant.  numpy's matmul is the only library primitive used; there is no
 blocking, fusion or online softmax here.
 
+Tree verification (Sec. 2.2 "Speculative Decoding", last paragraph; Sec. 4.1:
+the tree-verifying comparison system uses trees of 8 candidates): the candidate
+tokens of one step form a tree whose every root-to-node path is a possible
+continuation, all verified in one step.  The paper gives no more than that, so
+the definition here is the one that sentence fixes: a node is evaluated exactly
+as if its path alone had been submitted as a chain -- position = start + depth,
+visible keys = the prefix, its ancestors and itself.  Nodes are given in an
+order with parents first; `masks[i]` has bit j set when node j is node i or one
+of its ancestors.  Node i's keys/values are stored at cache row start + i; once
+a path has been accepted, `OracleMiddle.compact` moves its rows to the front of
+that range and drops the rest, after which the cache is what the chain would
+have left.
+
 Pins: tests/test_oracle_*.py (brute-force scalar loops, closed forms,
 chunk-split / verify-vs-sequential / batch-independence / rollback / RoPE-shift
-invariants, torch-CPU third opinions).  The paper prints no numeric worked
-example for this path, so no value here is pinned to a printed figure.
+invariants, torch-CPU third opinions; for trees: a chain-shaped tree equals the
+chain, every path of a tree equals that path submitted alone, compaction equals
+the chain's cache).  The paper prints no numeric worked example for this path,
+so no value here is pinned to a printed figure.
 """
 from __future__ import annotations
 
@@ -78,22 +93,64 @@ def prefix_causal_attention(q, K, V, start):
     return out
 
 
+def check_tree(masks):
+    """True if `masks` describes a forest in parents-first order: node i sees
+    itself, nothing after itself, and exactly the nodes on one path to it."""
+    for i, m in enumerate(masks):
+        m = int(m)
+        if m < 0 or (m >> i) != 1:            # own bit set, no later node
+            return False
+        anc = [j for j in range(i) if (m >> j) & 1]
+        seen = 0
+        for j in anc:                         # the ancestors form a path: each one's
+            if int(masks[j]) != (seen | (1 << j)):   # own mask = the ancestors before it + itself
+                return False
+            seen |= 1 << j
+    return True
+
+
+def tree_depths(masks):
+    """Depth of every node (a root has depth 0) = number of its ancestors."""
+    return np.array([bin(int(m)).count("1") - 1 for m in masks], dtype=np.int64)
+
+
+def tree_attention(q, K, V, start, masks):
+    """Attention of tree nodes: node t sees keys 0 .. start-1 (the prefix) and
+    the cache rows start + j of the nodes j on its path (bit j of masks[t]).
+
+    q: [n, H, hd]; K, V: [len, H, hd] with len >= start + n.
+    """
+    n, H, hd = q.shape
+    out = np.empty_like(q)
+    scale = 1.0 / np.sqrt(np.float64(hd))
+    for t in range(n):
+        rows = list(range(start)) + [start + j for j in range(n) if (int(masks[t]) >> j) & 1]
+        for h in range(H):
+            s = (K[rows, h, :] @ q[t, h, :]) * scale
+            w = np.exp(s - s.max())
+            w = w / w.sum()
+            out[t, h, :] = w @ V[rows, h, :]
+    return out
+
+
 def silu(z):
     return z / (1.0 + np.exp(-z))
 
 
-def decoder_layer(x, start, w, kv, cfg):
+def decoder_layer(x, start, w, kv, cfg, masks=None):
     """One decoder layer on one device's segment.
 
     x: [n, d] rows at positions start..start+n-1; w: dict of this layer's
     weights (linear weights stored [out, in]); kv: [K, V] lists of this
     device/layer, each [len, H, hd] with len == start on entry; they are
     extended in place (returned as new arrays in the list).
+    masks: None for consecutive rows (a chunk or a chain of draft tokens), or
+    the tree masks of the n rows (then row i is at position start + depth(i)).
     """
     n, d = x.shape
     H, hd = cfg["n_heads"], cfg["head_dim"]
     eps, theta = cfg["rms_eps"], cfg["rope_theta"]
-    pos = np.arange(start, start + n)
+    pos = np.arange(start, start + n) if masks is None else start + tree_depths(masks)
 
     xn = rmsnorm(x, w["attn_norm"], eps)
     q = (xn @ w["wq"].T).reshape(n, H, hd)
@@ -103,7 +160,10 @@ def decoder_layer(x, start, w, kv, cfg):
     k = rope_rotate_half(k, pos, theta)
     kv[0] = np.concatenate([kv[0], k], axis=0)
     kv[1] = np.concatenate([kv[1], v], axis=0)
-    o = prefix_causal_attention(q, kv[0], kv[1], start).reshape(n, d)
+    if masks is None:
+        o = prefix_causal_attention(q, kv[0], kv[1], start).reshape(n, d)
+    else:
+        o = tree_attention(q, kv[0], kv[1], start, masks).reshape(n, d)
     h = x + o @ w["wo"].T
     hn = rmsnorm(h, w["ffn_norm"], eps)
     a = silu(hn @ w["w_gate"].T) * (hn @ w["w_up"].T)
@@ -154,22 +214,41 @@ class OracleMiddle:
     def release(self, device):
         self.kv.pop(device, None)
 
+    def compact(self, device, base, keep):
+        """After a tree step at `base`: keep the nodes `keep` (indices into the
+        tree, one path from a root, ascending) as rows base .. base+len(keep)-1
+        and drop everything behind them."""
+        keep = [int(k) for k in keep]
+        if any(b <= a for a, b in zip(keep, keep[1:])) or (keep and keep[0] < 0):
+            raise ValueError("kept nodes must ascend")
+        if base < 0 or base + (keep[-1] + 1 if keep else 0) > self.kv_len(device):
+            raise ValueError("kept node beyond the cache")
+        self._ensure(device)
+        rows = list(range(base)) + [base + k for k in keep]
+        for l in range(self.cfg["n_layers"]):
+            self.kv[device][l][0] = self.kv[device][l][0][rows]
+            self.kv[device][l][1] = self.kv[device][l][1][rows]
+
     def forward(self, segments):
-        """segments: list of (device, start_pos, X[n, d]).  Returns list of [n, d].
+        """segments: list of (device, start_pos, X[n, d]) or, for a tree of
+        candidates, (device, start_pos, X[n, d], masks).  Returns list of [n, d].
 
         start_pos < cache length rolls the cache back to start_pos first (the
         rows of rejected draft tokens are dropped); start_pos > length is an
         error.  One device may appear once per step.
         """
         seen = set()
-        for dev, start, x in segments:
+        segments = [tuple(sg) + (None,) * (4 - len(sg)) for sg in segments]
+        for dev, start, x, masks in segments:
             if dev in seen:
                 raise ValueError("device appears twice in one step")
             seen.add(dev)
             if start > self.kv_len(dev):
                 raise ValueError("start position leaves a gap in the cache")
+            if masks is not None and (len(masks) != len(x) or not check_tree(masks)):
+                raise ValueError("masks do not describe a tree in parents-first order")
         xs = []
-        for dev, start, x in segments:
+        for dev, start, x, masks in segments:
             self._ensure(dev)
             for l in range(self.cfg["n_layers"]):
                 self.kv[dev][l][0] = self.kv[dev][l][0][:start]
@@ -179,6 +258,6 @@ class OracleMiddle:
         # step; segments never interact, so this equals device-by-device order.
         for l in range(self.cfg["n_layers"]):
             w = self._layer(l)
-            for i, (dev, start, _) in enumerate(segments):
-                xs[i] = decoder_layer(xs[i], start, w, self.kv[dev][l], self.cfg)
+            for i, (dev, start, _, masks) in enumerate(segments):
+                xs[i] = decoder_layer(xs[i], start, w, self.kv[dev][l], self.cfg, masks)
         return xs

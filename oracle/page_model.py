@@ -13,7 +13,9 @@ policy, and this file is an independent model of that policy:
     order; then segments allocate in array order, each in ascending position;
   * token at position q lives in the device's page-list entry q // page,
     slot q % page; a device owns exactly ceil(kv_len / page) pages;
-  * a step that fails validation or does not fit changes nothing.
+  * a step that fails validation or does not fit changes nothing;
+  * keeping one path of a tree step (compact) shortens the device to
+    base + kept nodes at once and frees, at once, the pages wholly beyond.
 
 Written with plain Python sets/lists; shares nothing with the library's planner.
 """
@@ -100,6 +102,28 @@ class PageModel:
             self.length[dev] = start + n
             targets.append(tgt)
         return targets
+
+    def compact(self, dev, base, keep):
+        """Keep tree nodes `keep` (ascending indices) of the step that started at
+        `base`.  Returns the (page, slot) moves as (source, destination) pairs."""
+        if not (0 <= dev < self.max_devices):
+            raise PageModelError(EDEVICE, "device id out of range")
+        keep = list(keep)
+        if base < 0 or len(keep) > self.max_verify or any(k < 0 or k >= self.max_verify for k in keep) \
+                or any(b <= a for a, b in zip(keep, keep[1:])):
+            raise PageModelError(EINVAL, "bad kept-node list")
+        length = self.length.get(dev, 0)
+        if base > length or (keep and base + keep[-1] >= length):
+            raise PageModelError(EPOS, "kept node beyond the cache")
+        lst = self.pages.get(dev, [])
+        moves = [((lst[(base + k) // self.page], (base + k) % self.page),
+                  (lst[(base + i) // self.page], (base + i) % self.page)) for i, k in enumerate(keep)]
+        new_len = base + len(keep)
+        while len(lst) > self._need(new_len):
+            self.free.add(lst.pop())
+        if dev in self.length or new_len:
+            self.length[dev] = new_len
+        return moves
 
     def release(self, dev):
         if not (0 <= dev < self.max_devices):

@@ -96,3 +96,31 @@ def test_policy_properties_under_random_traffic():
                 assert newp == min(free); free.remove(newp)
             assert t == [(P[q // 16], q % 16) for q in range(start, start + n)]
         assert free == pm.free
+
+
+def test_compact_hand_table():
+    pm = PageModel(n_pages=8)
+    pm.step([(0, 0, 0, 28)])                          # pages 0,1
+    pm.step([(0, 1, 28, 8)])                          # tree of 8 at 28..35 -> pages 0,1,2
+    assert pm.query(0) == (36, [0, 1, 2])
+    moves = pm.compact(0, 28, [1, 4, 6])              # rows 29, 32, 34 -> 28, 29, 30
+    assert moves == [((1, 13), (1, 12)), ((2, 0), (1, 13)), ((2, 2), (1, 14))]
+    assert pm.query(0) == (31, [0, 1]) and 2 in pm.free
+    pm.step([(1, 0, 0, 1)])                           # the freed page is the lowest free one again
+    assert pm.query(1) == (1, [2])
+    assert pm.compact(0, 31, []) == [] and pm.query(0) == (31, [0, 1])
+    assert pm.compact(0, 16, []) == [] and pm.query(0) == (16, [0])   # an empty keep list is a rollback
+
+
+def test_compact_errors_leave_state_untouched():
+    pm = PageModel(n_pages=8, max_devices=4)
+    pm.step([(0, 0, 0, 20)]); pm.step([(0, 1, 20, 4)])
+    snap = (pm.query(0), set(pm.free))
+    for args, code in (((9, 20, [0]), EDEVICE), ((0, 20, [1, 1]), EINVAL), ((0, 20, [2, 1]), EINVAL),
+                       ((0, 20, [-1]), EINVAL), ((0, 20, [8]), EINVAL), ((0, -1, [0]), EINVAL),
+                       ((0, 20, [4]), EPOS), ((0, 25, []), EPOS), ((0, 22, [0, 2]), EPOS)):
+        with pytest.raises(PageModelError) as e:
+            pm.compact(*args)
+        assert e.value.code == code, args
+        assert (pm.query(0), set(pm.free)) == snap
+    assert pm.compact(1, 0, []) == [] and pm.query(1) == (0, [])      # unknown device, nothing kept: no-op
