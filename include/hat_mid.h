@@ -59,7 +59,7 @@ typedef struct hat_mid hat_mid_t; /* opaque handle */
 
 typedef enum {
   HAT_OK = 0,
-  HAT_EINVAL = -1,  /* malformed argument (n <= 0, verify segment longer than 8, beyond max_pos ...) */
+  HAT_EINVAL = -1,  /* malformed argument (n <= 0, verify segment longer than 8, bad tree, beyond max_pos ...) */
   HAT_ENOMEM = -2,  /* KV pool exhausted for this step */
   HAT_EPOS = -3,    /* start_pos beyond the device's cache length (would leave a gap) */
   HAT_EDUP = -4,    /* the same device twice in one step */
@@ -104,7 +104,19 @@ typedef struct {
  * start_pos must satisfy 0 <= start_pos <= cache length of the device.
  * start_pos < length first rolls the cache back to start_pos: that is how the
  * rows of rejected draft tokens disappear (Sec. 3.4: the next round starts after
- * the last accepted token).  A device not seen before starts with length 0. */
+ * the last accepted token).  A device not seen before starts with length 0.
+ *
+ * Tree verification (Sec. 2.2, last paragraph: candidates combined into a tree whose
+ * every branch may be the accepted path; Sec. 4.1 uses trees of 8 for the
+ * tree-verifying comparison system): a VERIFY segment with tree_mask != NULL holds
+ * the n nodes of a forest in parents-first order.  tree_mask[i] has bit j set when
+ * node j is node i itself or one of its ancestors (bit i always, no bit above i, and
+ * the ancestors must be one path).  Node i is evaluated exactly as if its path had
+ * been submitted alone as a chain: its position is start_pos + depth(i) and it
+ * attends to the cache rows below start_pos, to its ancestors and to itself.  Its
+ * K/V row is stored at cache row start_pos + i, so the cache length becomes
+ * start_pos + n as for any segment; hat_mid_kv_compact then keeps the accepted path.
+ * tree_mask == NULL means consecutive rows (the chain mask (2 << i) - 1). */
 typedef struct {
   int32_t device_id;
   int32_t kind;           /* hat_seg_kind_t */
@@ -112,6 +124,7 @@ typedef struct {
   int32_t start_pos;
   const void* hidden_in;  /* device pointer, [n, d_model] row-major, io_dtype */
   void* hidden_out;       /* device pointer, [n, d_model] row-major, io_dtype; may equal hidden_in */
+  const uint8_t* tree_mask; /* HOST pointer to n bytes, or NULL; only with HAT_SEG_VERIFY */
 } hat_mid_segment_t;
 
 /* Bytes of KV pool / workspace the configuration needs (0 if cfg is invalid). */
@@ -146,6 +159,19 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
  * pageable memory the copies are still correct but serialise.  Validation,
  * errors and atomicity are those of hat_mid_forward. */
 hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream);
+
+/* After a tree step that started at base_pos: keeps the accepted path.  keep: host
+ * array of n_keep node indices of that step, strictly ascending (a path from a root,
+ * though only the order is checked), each < HAT_MAX_VERIFY and base_pos + keep[i]
+ * below the cache length.  In every layer the K/V row of node keep[i] moves to cache
+ * row base_pos + i (a pure copy: the node was rotated for position base_pos + depth,
+ * which is base_pos + i on its own path); the cache length becomes base_pos + n_keep
+ * and the pages wholly beyond it return to the pool at once.  n_keep == 0 is a plain
+ * rollback to base_pos.  Enqueues one small kernel on hip_stream; the next forward
+ * of the device on that stream starts at base_pos + n_keep.  On error nothing changes
+ * (HAT_EINVAL: bad list; HAT_EPOS: a row beyond the cache; HAT_EDEVICE). */
+hat_status_t hat_mid_kv_compact(hat_mid_t* h, int32_t device_id, int32_t base_pos, const int32_t* keep,
+                                int32_t n_keep, void* hip_stream);
 
 /* The device left (Sec. 2.1: requests leave the batch): all its pages return to
  * the pool, its length becomes 0.  Unknown-but-valid ids are a no-op. */

@@ -21,7 +21,7 @@ KERNEL_NAMES = ["gather", "rmsnorm", "gemm_qkv", "rope_append", "attn_chunk", "a
 DUMP_IDS = {"xnorm": 0, "q": 1, "attn": 2, "xnorm2": 3, "act": 4}
 EXPORTED_SYMBOLS = [
     "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_forward_host", "hat_mid_release",
-    "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_import", "hat_mid_kv_export",
+    "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_compact", "hat_mid_kv_import", "hat_mid_kv_export",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
     "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_plan",
     "hat_sched_create", "hat_sched_destroy", "hat_sched_observe", "hat_sched_mu", "hat_sched_predict",
@@ -43,7 +43,7 @@ class LayerWeights(C.Structure):
 
 class CSegment(C.Structure):
     _fields_ = [("device_id", C.c_int32), ("kind", C.c_int32), ("n", C.c_int32), ("start_pos", C.c_int32),
-                ("hidden_in", C.c_void_p), ("hidden_out", C.c_void_p)]
+                ("hidden_in", C.c_void_p), ("hidden_out", C.c_void_p), ("tree_mask", C.c_void_p)]
 
 
 class HatError(RuntimeError):
@@ -88,6 +88,8 @@ def load_library():
     lib.hat_mid_last_error.argtypes = [vp]
     lib.hat_mid_kv_query.restype = i32
     lib.hat_mid_kv_query.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(i32)]
+    lib.hat_mid_kv_compact.restype = i32
+    lib.hat_mid_kv_compact.argtypes = [vp, i32, i32, C.POINTER(i32), i32, vp]
     lib.hat_mid_kv_import.restype = i32
     lib.hat_mid_kv_import.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
     lib.hat_mid_kv_export.restype = i32
@@ -132,6 +134,7 @@ class Segment:
     start_pos: int
     hidden_in: "object"          # torch tensor [n, d] on the GPU
     hidden_out: "object" = None   # defaults to a fresh tensor
+    tree_mask: "object" = None    # verify segments only: one visibility byte per row (a list of ints), or None
 
 
 class HatMid:
@@ -183,18 +186,28 @@ class HatMid:
         if rc != 0:
             raise HatError(rc, self.lib.hat_mid_last_error(self._handle).decode())
 
+    @staticmethod
+    def _mask_ptr(seg, keep):
+        """Marshals a segment's tree mask into a byte array (kept alive in `keep` for the call)."""
+        if seg.tree_mask is None:
+            return None
+        buf = (C.c_uint8 * len(seg.tree_mask))(*[int(m) for m in seg.tree_mask])
+        keep.append(buf)
+        return C.cast(buf, C.c_void_p)
+
     def forward(self, segments, stream=None):
         """segments: list of Segment.  Returns the list of output tensors."""
         torch = self.torch
         n = len(segments)
         arr = (CSegment * max(n, 1))()
-        outs = []
+        outs, keep = [], []
         for i, s in enumerate(segments):
             x = s.hidden_in
             assert x.is_cuda and x.dtype == self.io_torch and x.is_contiguous() and x.shape[1] == self.d
             out = s.hidden_out if s.hidden_out is not None else torch.empty_like(x)
             outs.append(out)
-            arr[i] = CSegment(s.device_id, s.kind, x.shape[0], s.start_pos, x.data_ptr(), out.data_ptr())
+            arr[i] = CSegment(s.device_id, s.kind, x.shape[0], s.start_pos, x.data_ptr(), out.data_ptr(),
+                              self._mask_ptr(s, keep))
         self._check(self.lib.hat_mid_forward(self._handle, arr, n, self._stream(stream)))
         return outs
 
@@ -204,14 +217,15 @@ class HatMid:
         torch = self.torch
         n = len(segments)
         arr = (CSegment * max(n, 1))()
-        outs = []
+        outs, keep = [], []
         for i, s in enumerate(segments):
             x = s.hidden_in
             assert (not x.is_cuda) and x.dtype == self.io_torch and x.is_contiguous() and x.shape[1] == self.d
             out = s.hidden_out if s.hidden_out is not None else torch.empty_like(x, pin_memory=x.is_pinned())
             assert not out.is_cuda and out.is_contiguous()
             outs.append(out)
-            arr[i] = CSegment(s.device_id, s.kind, x.shape[0], s.start_pos, x.data_ptr(), out.data_ptr())
+            arr[i] = CSegment(s.device_id, s.kind, x.shape[0], s.start_pos, x.data_ptr(), out.data_ptr(),
+                              self._mask_ptr(s, keep))
         self._keep_host = (segments, outs)   # the copies are asynchronous
         self._check(self.lib.hat_mid_forward_host(self._handle, arr, n, self._stream(stream)))
         return outs
@@ -224,6 +238,10 @@ class HatMid:
 
     def release(self, device_id):
         self._check(self.lib.hat_mid_release(self._handle, device_id))
+
+    def kv_compact(self, device_id, base_pos, keep, stream=None):
+        arr = (C.c_int32 * max(len(keep), 1))(*[int(k) for k in keep])
+        self._check(self.lib.hat_mid_kv_compact(self._handle, device_id, base_pos, arr, len(keep), self._stream(stream)))
 
     def kv_query(self, device_id, cap=1 << 16):
         ln, npg = C.c_int32(), C.c_int32()

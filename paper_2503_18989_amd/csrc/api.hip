@@ -202,6 +202,21 @@ hat_status_t fail(hat_mid* h, hat_status_t st, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(h, HAT_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 
+// node i sees itself and nothing later; its ancestors are one path (each ancestor's own mask is
+// the ancestors before it plus itself)
+bool valid_tree(const uint8_t* m, int n) {
+  for (int i = 0; i < n; ++i) {
+    if ((m[i] >> i) != 1) return false;
+    unsigned path = 0;
+    for (int j = 0; j < i; ++j) {
+      if (!((m[i] >> j) & 1)) continue;
+      if (m[j] != (path | (1u << j))) return false;
+      path |= 1u << j;
+    }
+  }
+  return true;
+}
+
 int32_t take_lowest(hat_mid* h) {
   auto it = h->free_pages.begin();
   int32_t id = *it;
@@ -377,6 +392,38 @@ hat_status_t hat_mid_release(hat_mid_t* h, int32_t device_id) {
   return HAT_OK;
 }
 
+hat_status_t hat_mid_kv_compact(hat_mid_t* h, int32_t device_id, int32_t base_pos, const int32_t* keep,
+                                int32_t n_keep, void* hip_stream) {
+  if (!h) return HAT_EINVAL;
+  const hat_mid_config_t& c = h->cfg;
+  if (device_id < 0 || device_id >= c.max_devices) return fail(h, HAT_EDEVICE, "device id %d out of range", device_id);
+  if (base_pos < 0 || n_keep < 0 || n_keep > HAT_MAX_VERIFY || (n_keep > 0 && !keep))
+    return fail(h, HAT_EINVAL, "bad compact arguments");
+  for (int i = 0; i < n_keep; ++i)
+    if (keep[i] < 0 || keep[i] >= HAT_MAX_VERIFY || (i > 0 && keep[i] <= keep[i - 1]))
+      return fail(h, HAT_EINVAL, "kept nodes must be ascending indices below %d", HAT_MAX_VERIFY);
+  DeviceState& d = h->dev[device_id];
+  if (base_pos > d.len || (n_keep > 0 && base_pos + keep[n_keep - 1] >= d.len))
+    return fail(h, HAT_EPOS, "kept row beyond cache length %d", d.len);
+  HatRowMoves mv{};
+  for (int i = 0; i < n_keep; ++i) {
+    const int src = base_pos + keep[i], dst = base_pos + i;
+    if (src == dst) continue;
+    mv.src[mv.n] = d.pages[src >> 4] * 16 + (src & 15);
+    mv.dst[mv.n] = d.pages[dst >> 4] * 16 + (dst & 15);
+    ++mv.n;
+  }
+  HIP_TRY(h, hat_launch_kv_move(h->pool, h->layer_pool_elems, c.n_layers, c.n_pages, mv, c.n_heads, c.head_dim,
+                                (hipStream_t)hip_stream));
+  d.len = base_pos + n_keep;
+  const size_t want = (size_t)(d.len + 15) / 16;
+  while (d.pages.size() > want) {
+    h->free_pages.insert(d.pages.back());
+    d.pages.pop_back();
+  }
+  return HAT_OK;
+}
+
 hat_status_t hat_mid_kv_query(const hat_mid_t* h, int32_t device_id, int32_t* kv_len, int32_t* pages_out, int32_t cap,
                               int32_t* n_pages_out) {
   if (!h) return HAT_EINVAL;
@@ -409,6 +456,10 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
       return fail(h, HAT_EINVAL, "segment %d: bad kind/n/start", i);
     if (g.kind == HAT_SEG_VERIFY && g.n > HAT_MAX_VERIFY)
       return fail(h, HAT_EINVAL, "segment %d: verify segment of %d rows (max %d)", i, g.n, HAT_MAX_VERIFY);
+    if (g.tree_mask) {
+      if (g.kind != HAT_SEG_VERIFY) return fail(h, HAT_EINVAL, "segment %d: a tree needs a verify segment", i);
+      if (!valid_tree(g.tree_mask, g.n)) return fail(h, HAT_EINVAL, "segment %d: tree_mask is not a parents-first forest", i);
+    }
     if ((long)g.start_pos + g.n > c.max_pos) return fail(h, HAT_EINVAL, "segment %d: beyond max_pos", i);
     if (!g.hidden_in || !g.hidden_out) return fail(h, HAT_EINVAL, "segment %d: null hidden pointer", i);
     if (seen[g.device_id]) return fail(h, HAT_EDUP, "segment %d: device %d twice in one step", i, g.device_id);
@@ -485,8 +536,8 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
       memcpy(&P[o_out + 2 * i], &op, 8);
       for (size_t k = 0; k < d.pages.size(); ++k) P[o_pt + pt + k] = d.pages[k];
       for (int r = 0; r < g.n; ++r) {
-        const int q = g.start_pos + r;
-        P[o_pos + t] = q;
+        const int q = g.start_pos + r;   // cache row; also the position unless the rows form a tree
+        P[o_pos + t] = g.tree_mask ? g.start_pos + __builtin_popcount(g.tree_mask[r]) - 1 : q;
         P[o_dst + t] = d.pages[q >> 4] * 16 + (q & 15);
         P[o_tseg + t] = i;
         ++t;
@@ -542,6 +593,10 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
           it.start = segs[i].start_pos; it.tok0 = P[o_toff + i]; it.kv_len = len; it.pt_off = P[o_spt + i];
           it.kv_begin = k * step; it.kv_end = std::min(len, (k + 1) * step);
           it.part_row = ns > 1 ? part_row + k * segs[i].n : -1;
+          for (int r = 0; r < segs[i].n; ++r) {
+            const uint32_t vis = segs[i].tree_mask ? segs[i].tree_mask[r] : (2u << r) - 1;
+            (r < 4 ? it.vis_lo : it.vis_hi) |= vis << (8 * (r & 3));
+          }
           vitems.push_back(it);
         }
         if (ns > 1) {

@@ -5,7 +5,8 @@
 //             One workgroup = 256 query rows (8 waves x 32) of one head; K/V tiles
 //             of 64 keys are staged in LDS and shared by the eight waves.
 //   verify -- the draft sequence of a device in the decode phase verified in one
-//             step (Sec. 3.4): at most 8 query rows against a long cache, HBM
+//             step (Sec. 3.4), or a tree of candidates (Sec. 2.2) given as one
+//             visibility byte per row: at most 8 query rows against a long cache, HBM
 //             bound.  One workgroup = one (segment, head, key range); each wave
 //             streams every 4th pair of pages straight from global memory into
 //             MFMA operand registers (the page tiles are stored in operand order,
@@ -58,20 +59,25 @@ __device__ __forceinline__ SegInfo seg_info(const HatPlanDev& p, const HatAttnIt
 // Online-softmax update for one 32-key S^T tile held as 16 accumulator values.
 // key of value r: key0 + 8*(r/4) + 4*half + r%4.  Returns probabilities as the
 // two B operands (keys 0..15 / 16..31 of the tile) and rescales O when the running
-// maximum of any row of the wave moved.  MASK = false is for tiles that lie wholly
-// below every row's causal limit (no compares).  Scores are kept unscaled; the
+// maximum of any row of the wave moved.  MASK = 0 is for tiles that lie wholly
+// below every row's causal limit (no compares); 1 = causal (keys up to qpos); 2 = the
+// caller supplies the visibility of the lane's keys as a bit set (vis).  Scores are kept unscaled; the
 // softmax scale (times log2 e) is folded into the exponent's fma.
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-template <int NC, bool MASK>
+template <int NC, int MASK>
 __device__ __forceinline__ void softmax_step(const f32x16& s_acc, float scale_log2, int key0, int half, int qpos,
-                                             float& m_run, float& l_run, f32x16 (&o)[NC], f16x8& p0, f16x8& p1) {
+                                             float& m_run, float& l_run, f32x16 (&o)[NC], f16x8& p0, f16x8& p1,
+                                             uint32_t vis = 0) {
   float sr[16];
   float mx = -INFINITY;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    if (MASK) {
+    if (MASK == 1) {
       const int key = key0 + 8 * (r >> 2) + 4 * half + (r & 3);
       sr[r] = (key <= qpos) ? s_acc[r] : -INFINITY;
+    } else if (MASK == 2) {
+      // vis: this lane's 16 keys of the tile, bit 8*(r/4) + r%4 = key of value r visible
+      sr[r] = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s_acc[r] : -INFINITY;
     } else {
       sr[r] = s_acc[r];
     }
@@ -149,7 +155,7 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
   const int half = lane >> 5, n = lane & 31;
   const int qi = n < it.nq ? n : it.nq - 1;  // clamp idle columns onto a real row
   const int qrow = sg.tok0 + it.q0 + qi;
-  const int qpos = sg.start + it.q0 + qi;
+  const uint32_t vis = ((qi < 4 ? it.vis_lo : it.vis_hi) >> (8 * (qi & 3))) & 0xffu;  // q0 = 0 for verify items
   const float scale_log2 = kLog2e / sqrtf((float)HD);
 
   f16x8 qreg[NS];
@@ -209,8 +215,17 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
       }
     }
     f16x8 p0, p1;
-    if (key0 + 31 > sg.start + it.q0) softmax_step<NC, true>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
-    else softmax_step<NC, false>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+    if (key0 + 31 >= sg.start) {
+      // keys start-32 .. start+31 as one 64-bit set: the cache below the segment is visible, the
+      // segment's own rows as the query row's byte says, nothing beyond; the tile's 32 keys begin at
+      // bit key0 - start + 32 (1..39 here, as start - 31 <= key0 <= start + 7), and this lane
+      // holds keys 4*half + {0..3, 8..11, 16..19, 24..27} of them
+      const uint64_t window = ((uint64_t)vis << 32) | 0xffffffffull;
+      const uint32_t tile_vis = (uint32_t)(window >> (key0 - sg.start + 32)) >> (4 * half);
+      softmax_step<NC, 2>(sacc, scale_log2, key0, half, 0, m_run, l_run, o, p0, p1, tile_vis);
+    } else {
+      softmax_step<NC, 0>(sacc, scale_log2, key0, half, 0, m_run, l_run, o, p0, p1);
+    }
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[c], p0, o[c], 0, 0, 0);
@@ -400,8 +415,8 @@ __global__ __launch_bounds__(HAT_CHUNK_QROWS * 2) void attn_chunk_kernel(HatPlan
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kk, qreg[s], sacc, 0, 0, 0);
       }
       f16x8 p0, p1;
-      if (key0 + 31 > wave_first_pos) softmax_step<NC, true>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
-      else softmax_step<NC, false>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+      if (key0 + 31 > wave_first_pos) softmax_step<NC, 1>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
+      else softmax_step<NC, 0>(sacc, scale_log2, key0, half, qpos, m_run, l_run, o, p0, p1);
       const bool tail = key0 + 32 > sg.kv_len;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {

@@ -310,6 +310,28 @@ __global__ void kv_export_kernel(const bf16_t* __restrict__ pool, int n_pages, c
   *(bf16x8*)(v + so) = vv;
 }
 
+// One thread per (layer, head, octet of the head): applies the row moves in order.  The moves
+// of a kept tree path go to lower-or-equal rows in ascending order, so a destination is never a
+// source of a later move, and no two threads touch the same bytes.
+__global__ void kv_move_kernel(bf16_t* __restrict__ pool, size_t layer_elems, int L, int n_pages, HatRowMoves mv, int H,
+                               int hd) {
+  const int octs = hd >> 3;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)L * H * octs) return;
+  const int o = (int)(idx % octs);
+  const int hh = (int)((idx / octs) % H);
+  const int l = (int)(idx / ((size_t)octs * H));
+  bf16_t* base = pool + (size_t)l * layer_elems + (size_t)hh * n_pages * kv_head_elems(hd);
+  for (int m = 0; m < mv.n; ++m) {
+    bf16_t* sp = base + (size_t)(mv.src[m] >> 4) * kv_head_elems(hd);
+    bf16_t* dp = base + (size_t)(mv.dst[m] >> 4) * kv_head_elems(hd);
+    const int ss = mv.src[m] & 15, ds = mv.dst[m] & 15;
+    *(bf16x8*)(dp + ktile_index(ds, o * 8)) = *(const bf16x8*)(sp + ktile_index(ss, o * 8));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dp[16 * hd + vtile_index(ds, o * 8 + e)] = sp[16 * hd + vtile_index(ss, o * 8 + e)];
+  }
+}
+
 __global__ void unpack_p32_kernel(const act_t* __restrict__ srcP, int row_len, int col0, int ncols, int T,
                                   float* __restrict__ dst) {
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -368,6 +390,13 @@ hipError_t hat_launch_kv_export(const bf16_t* pool_layer, int n_pages, const int
                                 bf16_t* k, bf16_t* v, int H, int hd, hipStream_t st) {
   const size_t cnt = (size_t)n * H * (hd >> 3);
   kv_export_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
+  return hipGetLastError();
+}
+hipError_t hat_launch_kv_move(bf16_t* pool, size_t layer_elems, int L, int n_pages, const HatRowMoves& mv, int H,
+                              int hd, hipStream_t st) {
+  if (mv.n <= 0) return hipSuccess;
+  const size_t cnt = (size_t)L * H * (hd >> 3);
+  kv_move_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool, layer_elems, L, n_pages, mv, H, hd);
   return hipGetLastError();
 }
 hipError_t hat_launch_unpack_p32(const act_t* srcP, int row_len, int col0, int ncols, int T, float* dst,

@@ -105,7 +105,9 @@ struct HatAttnItem {
   int32_t tok0;      // batch row of the segment's first row
   int32_t kv_len;    // cache length after this step's append
   int32_t pt_off;    // offset of the segment's page list in page_tbl
-  int32_t pad0, pad1;
+  // verify items: byte i = visibility of the segment's new rows for query row i (bit j: the row
+  // stored at cache row start + j is visible); a chain has (2 << i) - 1.  Unused by chunk items.
+  uint32_t vis_lo, vis_hi;
 };
 struct HatMergeItem {
   int32_t row0;      // first batch row of this group
@@ -135,6 +137,13 @@ hipError_t hat_attn_init();
 // k, v: [n, H, hd] bf16 plain; pages: device array of the page ids covering the rows
 hipError_t hat_launch_kv_import(bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
                                 const bf16_t* k, const bf16_t* v, int H, int hd, hipStream_t st);
+// Row moves inside one device's cache, applied in order in every layer and head.
+struct HatRowMoves {
+  int32_t n;
+  int32_t src[HAT_MAX_VERIFY_ROWS], dst[HAT_MAX_VERIFY_ROWS];  // page*16 + slot
+};
+hipError_t hat_launch_kv_move(bf16_t* pool, size_t layer_elems, int L, int n_pages, const HatRowMoves& mv, int H,
+                              int hd, hipStream_t st);
 hipError_t hat_launch_kv_export(const bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
                                 bf16_t* k, bf16_t* v, int H, int hd, hipStream_t st);
 // P32 [., ncols_total] columns [col0, col0+ncols) -> fp32 row-major [T, ncols]

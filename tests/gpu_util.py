@@ -45,23 +45,34 @@ class Pair:
         self.counter = 0
 
     def step(self, segs, inputs=None):
-        """segs: list of (device, kind, start, n).  Returns (gpu outs, oracle outs) as numpy."""
+        """segs: list of (device, kind, start, n) or (device, kind, start, n, tree masks).
+        Returns (gpu outs, oracle outs) as numpy."""
         import torch
         from paper_2503_18989_amd import Segment
+        masks = [sg[4] if len(sg) > 4 else None for sg in segs]
+        segs = [tuple(sg[:4]) for sg in segs]
         xs = []
         for i, (dev, kind, start, n) in enumerate(segs):
             x = inputs[i] if inputs is not None else hi.hidden_rows(n, self.cfg["d_model"], self.seed, self.counter, dev)
             xs.append(x)
         self.counter += 1
         gsegs = []
-        for (dev, kind, start, n), x in zip(segs, xs):
+        for (dev, kind, start, n), x, m in zip(segs, xs, masks):
             xd = to_dev_bf16(x) if self.io_dtype == "bf16" else torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()
-            gsegs.append(Segment(dev, kind, start, xd))
+            gsegs.append(Segment(dev, kind, start, xd, tree_mask=m))
         outs = self.gpu.forward(gsegs)
         torch.cuda.synchronize()
-        refs = self.ref.forward([(dev, start, x) for (dev, kind, start, n), x in zip(segs, xs)])
+        refs = self.ref.forward([(dev, start, x, m) for (dev, kind, start, n), x, m in zip(segs, xs, masks)])
         self.pages.step(segs)
         return [to_np(o) for o in outs], refs
+
+    def compact(self, dev, base, keep):
+        """Keeps tree nodes `keep` of the step that started at `base`, on all three sides."""
+        import torch
+        self.gpu.kv_compact(dev, base, keep)
+        torch.cuda.synchronize()
+        self.ref.compact(dev, base, keep)
+        self.pages.compact(dev, base, keep)
 
     def check_pages(self, devices):
         for d in devices:
