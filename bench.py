@@ -12,7 +12,7 @@ Besides the contract line it reports, in the same JSON object:
   roofline      the dominant kernel class of that workload (by GPU time), timed
                 with HIP events on the launch stream inside the library
   kernels       every kernel class of the step: average duration and roofline
-  legs          chunk-attention MFMA fraction on a mixed-batch step and verify-
+  legs          (tree-verify step included) chunk-attention MFMA fraction on a mixed-batch step and verify-
                 attention HBM GB/s on a verify-heavy step (30 devices)
   chunk_size_sweep  13B-shaped model, 8192-row prompts, chunk sizes 64..1024, with the 8 devices batched
                 per step and with one device per step: GPU time per step against chunk size and prefix
@@ -219,6 +219,24 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
     out["verify_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
     tok, ms = m.last_step_stats()
     out["verify_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms}
+
+    # --- the same devices submitting a tree of 8 candidates each (the tree-verifying comparison
+    # system's step, Sec. 4.1) instead of a chain of 5: what the larger step costs on this engine
+    xt = [to_dev_bf16(hi.hidden_rows(8, d, SEED + 5, dev)) for dev in range(30)]
+    masks = hi.tree_masks(hi.MEDUSA_LIKE_TREE)
+
+    def tstep():
+        m.forward([Segment(dev, hi.VERIFY, lengths[dev], xt[dev], tree_mask=masks) for dev in range(30)])
+    for _ in range(3):
+        tstep()
+    prof_t = profile_classes(m, lambda: [tstep() for _ in range(8)])
+    fl, by = attn_work([(ln, 8) for ln in lengths], d)
+    sec = prof_t["attn_verify"][0]
+    tok_t, ms_t = m.last_step_stats()
+    out["tree_verify_attn"] = dict(roof(fl, by, sec), us_per_launch=sec * 1e6, algorithmic_bytes=by,
+                                   workload="30 devices x tree of 8, same caches")
+    out["tree_verify_step"] = {"tokens": tok_t, "gpu_ms_for_%d_layers" % n_layers: ms_t,
+                               "ms_ratio_to_chain_of_5": ms_t / ms}
     m.close()
     del m
     torch.cuda.empty_cache()
