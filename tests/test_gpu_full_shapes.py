@@ -190,6 +190,63 @@ def test_cfg4_7b_verify_heavy_64_steps_with_rollback():
     gpu.close()
 
 
+def test_tree_decoding_7b_30_devices_16_steps():
+    """The verify-heavy shape with trees (Sec. 2.2 / 4.1: 8 candidates per step): 30 devices,
+    cache lengths U[1024,8192]; every step each device submits a seeded random tree of 8 and then
+    keeps a seeded random path of it (or nothing).  Page state of all 30 devices against the page
+    model after every step and every compaction; the oracle follows 3 devices through all steps."""
+    import torch
+    from oracle import OracleMiddle, PageModel
+    from paper_2503_18989_amd import Segment
+    cfg = hi.with_layers(hi.MID7B, 2)
+    seed = 4100
+    H, hd, d = cfg["n_heads"], cfg["head_dim"], cfg["d_model"]
+    lengths = list(hi.verify_lengths(seed))
+    steps = 16
+    n_pages = sum((ln + steps * 8 + 15) // 16 for ln in lengths) + 32
+    max_pos = 8192 + steps * 8 + 16
+    gpu, weights = build(cfg, seed, n_pages=n_pages, max_devices=30, max_step_tokens=256, max_pos=max_pos)
+    ref = OracleMiddle(cfg, weights)
+    pm = PageModel(n_pages, max_devices=30, max_step_tokens=16384, max_pos=max_pos)
+    order = np.argsort(lengths)
+    sampled = {int(order[0]), int(order[15]), int(order[-1])}
+    for dev in range(30):
+        pm.step([(dev, 0, 0, lengths[dev])])
+        for l in range(cfg["n_layers"]):
+            if dev in sampled:
+                k, v = hi.kv_prefix(lengths[dev], H, hd, seed, dev, l)
+                gpu.kv_import(dev, l, 0, to_dev_bf16(k).view(-1, H, hd), to_dev_bf16(v).view(-1, H, hd))
+                ref.import_kv(dev, l, 0, k, v)
+            else:
+                k, v = device_random_kv(lengths[dev], H, hd, seed * 100 + dev * 4 + l)
+                gpu.kv_import(dev, l, 0, k, v)
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    for it in range(steps):
+        trees = [hi.random_tree(seed, 8, it, dev) for dev in range(30)]
+        xs = [hi.hidden_rows(8, d, seed, it, dev) for dev in range(30)]
+        outs = gpu.forward([Segment(dev, hi.VERIFY, lengths[dev], to_dev_bf16(xs[dev]), tree_mask=hi.tree_masks(trees[dev]))
+                            for dev in range(30)])
+        torch.cuda.synchronize()
+        pm.step([(dev, hi.VERIFY, lengths[dev], 8) for dev in range(30)])
+        refs = ref.forward([(dev, lengths[dev], xs[dev], hi.tree_masks(trees[dev])) for dev in sorted(sampled)])
+        for dev, r in zip(sorted(sampled), refs):
+            worst = max(worst, check(to_np(outs[dev]), r, "step %d device %d" % (it, dev)))
+        for dev in range(30):
+            node = int(rng.integers(-1, 8))
+            keep = hi.tree_path(trees[dev], node) if node >= 0 else []
+            gpu.kv_compact(dev, lengths[dev], keep)
+            pm.compact(dev, lengths[dev], keep)
+            if dev in sampled:
+                ref.compact(dev, lengths[dev], keep)
+            lengths[dev] += len(keep)
+        torch.cuda.synchronize()
+        for dev in range(30):
+            assert gpu.kv_query(dev) == pm.query(dev), "step %d device %d" % (it, dev)
+    print("tree decoding: %d steps, worst rel err %.3e" % (steps, worst))
+    gpu.close()
+
+
 @pytest.mark.parametrize("chunk", [64, 128, 256, 512, 1024])
 def test_cfg5_13b_last_chunk_of_each_size(chunk):
     """13B width (d 5120, 40 heads, FFN 13824), 2 layers: 8 devices with 8192-row prompts,

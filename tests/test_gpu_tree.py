@@ -164,3 +164,21 @@ def test_verify_over_tiny_caches(start):
     check(*p.step([(0, hi.VERIFY, start, 8), (1, hi.VERIFY, start, 8, tree(hi.MEDUSA_LIKE_TREE))]), tol=6e-3)
     p.check_pages([0, 1])
     p.close()
+
+
+def test_tree_steps_fed_from_host_memory():
+    # the host-fed entry point carries the tree masks through: same bits as the device-fed call
+    import torch
+    from paper_2503_18989_amd import Segment
+    pa = Pair(SMALL64, 46, n_pages=40, max_devices=4, max_step_tokens=256, max_pos=512)
+    pb = Pair(SMALL64, 46, n_pages=40, max_devices=4, max_step_tokens=256, max_pos=512)
+    x0 = hi.hidden_rows(50, 256, 46, 0); x1 = hi.hidden_rows(8, 256, 46, 1)
+    masks = tree(hi.MEDUSA_LIKE_TREE)
+    for p_, host in ((pa, False), (pb, True)):
+        f = p_.gpu.forward_host if host else p_.gpu.forward
+        mk = (lambda x: to_dev_bf16(x).cpu().pin_memory()) if host else to_dev_bf16
+        f([Segment(0, hi.CHUNK, 0, mk(x0))])
+        p_.out = f([Segment(0, hi.VERIFY, 50, mk(x1), tree_mask=masks)])[0]
+        torch.cuda.synchronize()
+    assert torch.equal(pa.out.cpu(), pb.out.cpu())
+    pa.close(); pb.close()
