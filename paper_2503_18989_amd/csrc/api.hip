@@ -96,7 +96,7 @@ struct Buffers {
   float* resid;
   act_t *xn, *xn2, *qkv, *attn, *act;
   float2* table;
-  float* part_o;
+  act_t* part_o;
   float2* part_ml;
   float* gemm_part;
   int32_t* plan_dev;
@@ -125,7 +125,7 @@ size_t carve(const hat_mid_config_t& c, const Shapes& s, void* base, Buffers* ou
   b.attn = cv.take<act_t>((size_t)s.Tcap * s.d);
   b.act = cv.take<act_t>((size_t)s.Tcap * s.Fpad);
   b.table = cv.take<float2>((size_t)s.Tcap * (s.hd / 2));
-  b.part_o = cv.take<float>((size_t)s.part_rows_cap * s.d);
+  b.part_o = cv.take<act_t>((size_t)s.part_rows_cap * s.d);
   b.part_ml = cv.take<float2>((size_t)s.part_rows_cap * s.H);
   b.gemm_part = cv.take<float>((size_t)s.gemm_part_rows * s.d);
   b.plan_dev = cv.take<int32_t>(s.plan_words);

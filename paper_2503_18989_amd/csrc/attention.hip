@@ -21,8 +21,8 @@
 // exchange between the two lane halves, and the probabilities are already in the
 // B-operand order of O^T += V^T P^T (the V tile is stored in that key order).
 // Row at position p sees keys 0..p of its own device.  Long key ranges may be
-// split over several workgroups; those write (max, sum, unnormalised O) partials
-// that attn_merge combines.
+// split over several workgroups; those write (max, sum, O normalised by that sum, fp16)
+// partials that attn_merge combines.
 #include <hip/hip_runtime.h>
 
 #include "hat_device_util.h"
@@ -273,8 +273,14 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
       for (int x = 0; x < 4; ++x) ov[x] = to_act(acc[x] * inv);
       *(f16x4*)(a.outP + p32_index(sg.tok0 + it.q0 + q, head * HD + e, a.d)) = ov;
     } else {
+      // a partial result travels normalised by its own sum, in the activation type: the merge
+      // weighs it by that sum.  A key range that this row does not see at all has L = 0.
       const size_t pr = (size_t)(it.part_row + q) * a.H + head;
-      *(f32x4*)(a.part_o + pr * HD + e) = acc;
+      const float inv = L > 0.f ? 1.0f / L : 0.f;
+      f16x4 ov;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) ov[x] = to_act(acc[x] * inv);
+      *(f16x4*)(a.part_o + pr * HD + e) = ov;
       if (e == 0) a.part_ml[pr] = make_float2(M, L);
     }
   }
@@ -598,14 +604,15 @@ __global__ __launch_bounds__(HAT_CHUNK_QROWS * 2) void attn_chunk_kernel(HatPlan
         }
     } else {
       const size_t prow = (size_t)(it.part_row + 32 * wave + n) * a.H + head;
+      const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;   // 0: this key range lies beyond the row's position
 #pragma unroll
       for (int c = 0; c < NC; ++c)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          f32x4 ov;
+          f16x4 ov;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) ov[e] = o[c][4 * g + e];
-          *(f32x4*)(a.part_o + prow * HD + 32 * c + 8 * g + 4 * half) = ov;
+          for (int e = 0; e < 4; ++e) ov[e] = to_act(o[c][4 * g + e] * inv);
+          *(f16x4*)(a.part_o + prow * HD + 32 * c + 8 * g + 4 * half) = ov;
         }
       if (half == 0) a.part_ml[prow] = make_float2(m_run, l_run);
     }
@@ -628,14 +635,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(HatAttn a, const HatMer
     for (int s = 0; s < it.nsplit; ++s) {
       const size_t pr = (size_t)(it.part_row + s * it.stride + r) * a.H + head;
       const float2 ml = a.part_ml[pr];
-      const float f = exp2f(ml.x - M);
-      L += ml.y * f;
-      const f32x4 v0 = *(const f32x4*)(a.part_o + pr * HD + e), v1 = *(const f32x4*)(a.part_o + pr * HD + e + 4);
+      const float f = ml.y * exp2f(ml.x - M);   // weight of this key range: its sum, on the common scale
+      L += f;
+      const f16x8 v = *(const f16x8*)(a.part_o + pr * HD + e);
 #pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        acc[x] += v0[x] * f;
-        acc[4 + x] += v1[x] * f;
-      }
+      for (int x = 0; x < 8; ++x) acc[x] += (float)v[x] * f;
     }
     const float inv = 1.0f / L;
     f16x8 ov;

@@ -121,7 +121,7 @@ struct HatAttn {
   const act_t* qkv;          // P32 [., 3d]; q = columns [0, d)
   const bf16_t* pool_layer;  // this layer's pages
   act_t* outP;               // P32 [., d]
-  float* part_o;             // [part rows][H][hd] unnormalised partial outputs
+  act_t* part_o;             // [part rows][H][hd] partial outputs, each normalised by its own sum
   float2* part_ml;           // [part rows][H] (running max in log2 units, sum)
   const HatAttnItem* items;
   int n_items;
