@@ -175,37 +175,53 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
   const bf16_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
   const size_t page_stride = REC;
 
-  // Two register stages of raw page data: the loads of this wave's next page pair are in
-  // flight while the current pair is widened, multiplied and soft-maxed.
-  u32x4 kraw[1][NS], varaw[1][NC], vbraw[1][NC];
-  auto load_pair = [&](int pp, int st) {
+  // One register stage of raw page data per wave, refilled as early as possible: the loads of
+  // the wave's next page pair are issued as soon as the current pair has been widened out of the
+  // raw registers, and travel while the current pair is soft-maxed and multiplied.  Two
+  // workgroups share a CU (<= 256 VGPRs).
+  u32x4 kraw[NS], varaw[NC], vbraw[NC];
+  const bf16_t *recA = pool, *recB = pool;
+  auto page_recs = [&](int pp) {   // wave-uniform: scalar loads of the two page ids
     int ia = 2 * pp, ib = 2 * pp + 1;
     ib = ib < sg.npages ? ib : sg.npages - 1;
-    const bf16_t* recA = pool + (size_t)sg.pt[ia] * page_stride;
-    const bf16_t* recB = pool + (size_t)sg.pt[ib] * page_stride;
+    recA = pool + (size_t)sg.pt[ia] * page_stride;
+    recB = pool + (size_t)sg.pt[ib] * page_stride;
+  };
+  auto load_k = [&]() {
     const bf16_t* krec = (n < 16) ? recA : recB;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) kraw[st][s] = *(const u32x4*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8);
+    for (int s = 0; s < NS; ++s) kraw[s] = *(const u32x4*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8);
+  };
+  auto load_v = [&]() {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      varaw[st][c] = *(const u32x4*)(recA + 16 * HD + c * 512 + lane * 8);
-      vbraw[st][c] = *(const u32x4*)(recB + 16 * HD + c * 512 + lane * 8);
+      varaw[c] = *(const u32x4*)(recA + 16 * HD + c * 512 + lane * 8);
+      vbraw[c] = *(const u32x4*)(recB + 16 * HD + c * 512 + lane * 8);
     }
   };
-  auto compute_pair = [&](int pp, int st) {
+  int pp = pair0 + wave;
+  if (pp < pair1) {
+    page_recs(pp);
+    load_k();
+    load_v();
+  }
+  for (; pp < pair1; pp += 4) {
     const int key0 = pp << 5;
-    f16x8 kreg[NS], va[NC], vb[NC];
-#pragma unroll
-    for (int s = 0; s < NS; ++s) kreg[s] = kv_to_f16(kraw[st][s]);
     f32x16 sacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kreg[s], qreg[s], sacc, 0, 0, 0);
+    for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kv_to_f16(kraw[s]), qreg[s], sacc, 0, 0, 0);
+    f16x8 va[NC], vb[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      va[c] = kv_to_f16(varaw[st][c]);
-      vb[c] = kv_to_f16(vbraw[st][c]);
+      va[c] = kv_to_f16(varaw[c]);
+      vb[c] = kv_to_f16(vbraw[c]);
+    }
+    if (pp + 4 < pair1) {
+      page_recs(pp + 4);
+      load_k();
+      load_v();
     }
     if (key0 + 32 > sg.kv_len) {
 #pragma unroll
@@ -231,12 +247,6 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
       o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[c], p0, o[c], 0, 0, 0);
       o[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb[c], p1, o[c], 0, 0, 0);
     }
-  };
-  // one register stage per wave; two workgroups share a CU (<= 256 VGPRs), so one wave's
-  // loads are in flight while the other wave on the SIMD computes
-  for (int pp = pair0 + wave; pp < pair1; pp += 4) {
-    load_pair(pp, 0);
-    compute_pair(pp, 0);
   }
   l_run += __shfl_xor(l_run, 32);
 
