@@ -64,7 +64,7 @@ typedef enum {
   HAT_EPOS = -3,    /* start_pos beyond the device's cache length (would leave a gap) */
   HAT_EDUP = -4,    /* the same device twice in one step */
   HAT_EDEVICE = -5, /* device id outside [0, max_devices) */
-  HAT_EHIP = -6     /* a HIP runtime call failed */
+  HAT_EHIP = -6     /* a HIP runtime call or a host allocation failed */
 } hat_status_t;
 
 typedef enum { HAT_SEG_CHUNK = 0, HAT_SEG_VERIFY = 1 } hat_seg_kind_t;

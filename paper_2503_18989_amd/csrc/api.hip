@@ -281,8 +281,8 @@ size_t hat_mid_workspace_bytes(const hat_mid_config_t* cfg) {
   return carve(*cfg, s, nullptr, nullptr);
 }
 
-hat_status_t hat_mid_create(const hat_mid_config_t* cfg, const hat_mid_layer_weights_t* layers, void* kv_pool,
-                            void* workspace, void* hip_stream, hat_mid_t** out) {
+static hat_status_t create_impl(const hat_mid_config_t* cfg, const hat_mid_layer_weights_t* layers, void* kv_pool,
+                                void* workspace, void* hip_stream, hat_mid_t** out) {
   if (out) *out = nullptr;
   if (!out || !valid_cfg(cfg) || !layers || !kv_pool || !workspace) return HAT_EINVAL;
   if (((uintptr_t)kv_pool | (uintptr_t)workspace) & 255) return HAT_EINVAL;
@@ -436,7 +436,7 @@ hat_status_t hat_mid_kv_query(const hat_mid_t* h, int32_t device_id, int32_t* kv
   return HAT_OK;
 }
 
-hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
+static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
   if (!h) return HAT_EINVAL;
   if (n_segs == 0) return HAT_OK;  // an empty step: no work, no state change
   if (!segs || n_segs < 0) return fail(h, HAT_EINVAL, "no segments");
@@ -741,6 +741,26 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
   return HAT_OK;
 }
 
+// No exception crosses the ABI: the entry points that allocate host memory (vectors, the handle)
+// turn an allocation failure into a status.
+hat_status_t hat_mid_create(const hat_mid_config_t* cfg, const hat_mid_layer_weights_t* layers, void* kv_pool,
+                            void* workspace, void* hip_stream, hat_mid_t** out) {
+  try {
+    return create_impl(cfg, layers, kv_pool, workspace, hip_stream, out);
+  } catch (...) {
+    if (out) *out = nullptr;
+    return HAT_EHIP;
+  }
+}
+
+hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
+  try {
+    return forward_impl(h, segs, n_segs, hip_stream);
+  } catch (...) {
+    return fail(h, HAT_EHIP, "host allocation failed while planning the step");
+  }
+}
+
 hat_status_t hat_mid_last_step_stats(hat_mid_t* h, int32_t* tokens, float* gpu_ms) {
   if (!h) return HAT_EINVAL;
   if (!h->have_step) return fail(h, HAT_EINVAL, "no step has run yet");
@@ -782,7 +802,7 @@ static hat_status_t fixture_pages(hat_mid_t* h, const DeviceState& d, int pos0, 
   return HAT_OK;
 }
 
-hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
+static hat_status_t forward_host_impl(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
   if (!h) return HAT_EINVAL;
   if (n_segs == 0) return HAT_OK;
   if (!segs || n_segs < 0) return fail(h, HAT_EINVAL, "no segments");
@@ -814,7 +834,7 @@ hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, i
   }
   HIP_TRY(h, hipEventRecord(h->up_done[slot], h->copy_stream));
   HIP_TRY(h, hipStreamWaitEvent(st, h->up_done[slot], 0));
-  const hat_status_t rc = hat_mid_forward(h, dsegs.data(), n_segs, hip_stream);
+  const hat_status_t rc = forward_impl(h, dsegs.data(), n_segs, hip_stream);
   HIP_TRY(h, hipEventRecord(h->slot_free[slot], st));
   h->slot_used[slot] = true;
   if (rc != HAT_OK) return rc;
@@ -825,6 +845,14 @@ hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, i
     off += nb;
   }
   return HAT_OK;
+}
+
+hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
+  try {
+    return forward_host_impl(h, segs, n_segs, hip_stream);
+  } catch (...) {
+    return fail(h, HAT_EHIP, "host allocation failed while planning the step");
+  }
 }
 
 hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n, const void* k,
