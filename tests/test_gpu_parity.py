@@ -64,6 +64,39 @@ def test_tiny_stage_dumps_match_oracle_stages():
     p.close()
 
 
+def test_stage_dumps_hd128_chunk_and_tree_verify_in_one_step():
+    # per-kernel parity at head_dim 128: norm, QKV + rotary, chunk attention (300 rows over a 200-row
+    # prefix) and verify attention (a tree of 8 over the same prefix), FFN norm, SwiGLU activation
+    from oracle import decoder as od
+    cfg = dict(SMALL128, n_layers=1)
+    d, H, hd = cfg["d_model"], cfg["n_heads"], cfg["head_dim"]
+    p = Pair(cfg, 8, n_pages=80, gain_jitter=0.2, max_devices=2, max_step_tokens=512, max_pos=1024)
+    w = {k: v.astype(np.float64) for k, v in p.weights[0].items()}
+    p.step([(0, hi.CHUNK, 0, 200), (1, hi.CHUNK, 0, 200)])
+    xa = hi.hidden_rows(300, d, 8, 200).astype(np.float64); xb = hi.hidden_rows(8, d, 8, 201).astype(np.float64)
+    masks = hi.tree_masks(hi.MEDUSA_LIKE_TREE)
+    outs, refs = p.step([(0, hi.CHUNK, 200, 300), (1, hi.VERIFY, 200, 8, masks)], inputs=[xa, xb])
+    stages = {k: [] for k in ("xnorm", "q", "attn", "xnorm2", "act")}
+    for dev, x, pos, mk in ((0, xa, np.arange(200, 500), None), (1, xb, 200 + od.tree_depths(masks), masks)):
+        n = len(x)
+        xn = od.rmsnorm(x, w["attn_norm"], cfg["rms_eps"])
+        q = od.rope_rotate_half((xn @ w["wq"].T).reshape(n, H, hd), pos, cfg["rope_theta"])
+        K, V = p.ref.kv[dev][0]
+        o = (od.prefix_causal_attention(q, K, V, 200) if mk is None else od.tree_attention(q, K, V, 200, mk)).reshape(n, d)
+        hmid = x + o @ w["wo"].T
+        xn2 = od.rmsnorm(hmid, w["ffn_norm"], cfg["rms_eps"])
+        act = od.silu(xn2 @ w["w_gate"].T) * (xn2 @ w["w_up"].T)
+        for k, v in (("xnorm", xn), ("q", q.reshape(n, d)), ("attn", o), ("xnorm2", xn2), ("act", act)):
+            stages[k].append(v)
+    for name, parts in stages.items():
+        ref = np.concatenate(parts)
+        got = to_np(p.gpu.debug_dump(name, 308))
+        assert rel_err(got, ref) < 6e-3, (name, rel_err(got, ref))
+        assert rel_err(got[300:], ref[300:]) < 6e-3, (name, "tree rows", rel_err(got[300:], ref[300:]))
+    check(outs, refs)
+    p.close()
+
+
 @pytest.mark.parametrize("T", [1, 5, 31, 33, 70, 130, 260, 300])
 def test_ragged_row_counts_cover_every_gemm_tile(T):
     p = Pair(SMALL64, 11, n_pages=64, max_devices=2, max_step_tokens=512, max_pos=1024)
