@@ -215,6 +215,7 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
     fl, by = attn_work([(ln, 5) for ln in lengths], d)
     sec = prof["attn_verify"][0]
     out["verify_attn"] = dict(roof(fl, by, sec), us_per_launch=sec * 1e6, algorithmic_bytes=by,
+                              traffic=recorded_leg_traffic("attn_verify_kernel<128>"),
                               workload="30 devices x 5 rows, cache lengths U[1024,8192], 7B-shaped layer")
     out["verify_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
     tok, ms = m.last_step_stats()
@@ -382,6 +383,20 @@ def recorded_traffic(kernel):
 
 
 # ---------------------------------------------------------------- CPU baseline (oracle)
+def recorded_leg_traffic(kernel):
+    """HBM bytes per launch of an attention kernel in the legs (the first, i.e. largest, row of that kernel in
+    profiles/traffic_attention_legs.txt: fetched + written bytes, counters scaled by the copy calibration)."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "traffic_attention_legs.txt")
+    try:
+        for line in open(path):
+            if line.startswith(kernel):
+                f = dict(kv.split("=") for kv in line.split()[1:])
+                return float(f["fetch_bytes"]) + float(f["write_bytes"])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg7, weights, n_layers=6, n_chunks=8, chunk=256):
     from oracle import OracleMiddle
     try:
