@@ -182,3 +182,68 @@ def test_tree_steps_fed_from_host_memory():
         torch.cuda.synchronize()
     assert torch.equal(pa.out.cpu(), pb.out.cpu())
     pa.close(); pb.close()
+
+
+def test_long_mixed_run_all_features():
+    # 150 steps over 10 devices mixing everything the boundary offers: prompt chunks, chains with
+    # rollback, trees with path compaction, departures, and some steps fed from host memory; outputs
+    # against the oracle and page state against the page model at every step
+    import torch
+    from paper_2503_18989_amd import Segment
+    rng = np.random.default_rng(99)
+    cfg, ndev, max_pos, max_step = SMALL64, 10, 1536, 1024
+    p = Pair(cfg, 199, n_pages=ndev * max_pos // 16 // 2, max_devices=ndev, max_step_tokens=max_step, max_pos=max_pos)
+    ln = [0] * ndev
+    worst = 0.0
+    for step in range(150):
+        segs, trees, rows = [], {}, 0
+        for d in map(int, rng.permutation(ndev)):
+            r = rng.random()
+            if r < 0.3:
+                continue
+            if (r < 0.36 and ln[d] > 0) or ln[d] + 300 > max_pos:
+                p.gpu.release(d); p.ref.release(d); p.pages.release(d); ln[d] = 0
+                continue
+            if ln[d] == 0 or r < 0.5:
+                n = int(min(rng.choice([3, 16, 31, 64, 130, 256, 290]), max_step - rows))
+                if n <= 0:
+                    continue
+                segs.append((d, hi.CHUNK, ln[d], n)); ln[d] += n
+            elif r < 0.75:
+                back = int(min(rng.integers(0, 4), ln[d]))
+                n = int(min(rng.integers(1, 9), max_step - rows))
+                if n <= 0:
+                    continue
+                segs.append((d, hi.VERIFY, ln[d] - back, n)); ln[d] += n - back
+            else:
+                n = int(min(rng.integers(1, 9), max_step - rows))
+                if n <= 0:
+                    continue
+                trees[d] = hi.random_tree(199, n, step, d)
+                segs.append((d, hi.VERIFY, ln[d], n, hi.tree_masks(trees[d])))
+            rows += segs[-1][3]
+        if not segs:
+            continue
+        if step % 5 == 4:     # this step arrives from pinned host memory
+            xs = [hi.hidden_rows(sg[3], cfg["d_model"], 199, step, sg[0]) for sg in segs]
+            gs = [Segment(sg[0], sg[1], sg[2], to_dev_bf16(x).cpu().pin_memory(), tree_mask=sg[4] if len(sg) > 4 else None)
+                  for sg, x in zip(segs, xs)]
+            outs = p.gpu.forward_host(gs)
+            torch.cuda.synchronize()
+            outs = [to_np(o) for o in outs]
+            refs = p.ref.forward([(sg[0], sg[2], x, sg[4] if len(sg) > 4 else None) for sg, x in zip(segs, xs)])
+            p.pages.step([tuple(sg[:4]) for sg in segs])
+        else:
+            outs, refs = p.step(segs)
+        for o, r_ in zip(outs, refs):
+            e = rel_err(o, r_)
+            worst = max(worst, e)
+            assert np.all(np.isfinite(o)) and e <= TOL, (step, e)
+        for d, parents in trees.items():
+            node = int(rng.integers(-1, len(parents)))
+            keep = hi.tree_path(parents, node) if node >= 0 else []
+            p.compact(d, ln[d], keep); ln[d] += len(keep)
+        p.check_pages(range(ndev))
+        assert [p.gpu.kv_query(d)[0] for d in range(ndev)] == ln
+    print("long run: worst rel err %.3e" % worst)
+    p.close()
