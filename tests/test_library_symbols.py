@@ -58,3 +58,23 @@ def test_binding_refuses_to_run_without_gpu():
     import hat_inputs as hi
     with pytest.raises(RuntimeError):
         HatMid(hi.TINY, [], n_pages=4)
+
+
+def test_headers_compile_as_plain_c99(tmp_path):
+    """The boundary is a C ABI: both headers must be usable from a plain C99 translation unit, and the
+    segment struct must have the layout the Python binding marshals (4 x int32 + 3 pointers)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    src = tmp_path / "abi.c"
+    src.write_text('#include "hat_mid.h"\n#include "hat_sched.h"\n'
+                   'int main(void) { return (sizeof(hat_mid_segment_t) == 40 && sizeof(hat_mid_config_t) == 52) ? 0 : 1; }\n')
+    exe = tmp_path / "abi"
+    b = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                        str(src), "-o", str(exe)], capture_output=True, text=True)
+    assert b.returncode == 0, b.stderr
+    assert subprocess.run([str(exe)]).returncode == 0
+    from paper_2503_18989_amd.binding import CSegment, Config
+    import ctypes
+    assert ctypes.sizeof(CSegment) == 40 and ctypes.sizeof(Config) == 52
