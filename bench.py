@@ -219,7 +219,8 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
                               workload="30 devices x 5 rows, cache lengths U[1024,8192], 7B-shaped layer")
     out["verify_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
     tok, ms = m.last_step_stats()
-    out["verify_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms}
+    out["verify_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms,
+                          "hidden_tokens_per_s_extrapolated_to_30_layers": tok / (ms * 1e-3 / n_layers * 30)}
 
     # --- the same devices submitting a tree of 8 candidates each (the tree-verifying comparison
     # system's step, Sec. 4.1) instead of a chain of 5: what the larger step costs on this engine
@@ -237,6 +238,7 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
     out["tree_verify_attn"] = dict(roof(fl, by, sec), us_per_launch=sec * 1e6, algorithmic_bytes=by,
                                    workload="30 devices x tree of 8, same caches")
     out["tree_verify_step"] = {"tokens": tok_t, "gpu_ms_for_%d_layers" % n_layers: ms_t,
+                               "hidden_tokens_per_s_extrapolated_to_30_layers": tok_t / (ms_t * 1e-3 / n_layers * 30),
                                "ms_ratio_to_chain_of_5": ms_t / ms}
     m.close()
     del m
@@ -267,7 +269,8 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
     out["mixed_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
     out["mixed_step_gemm_mfma_frac"] = {k: gw[k][0] / prof[k][0] / PEAK_MFMA_BF16 for k in gw}
     tok, ms = m.last_step_stats()
-    out["mixed_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms}
+    out["mixed_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms,
+                         "hidden_tokens_per_s_extrapolated_to_30_layers": tok / (ms * 1e-3 / n_layers * 30)}
     m.close()
     return out
 
