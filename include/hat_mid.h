@@ -250,6 +250,29 @@ typedef enum {
  * forward on the same stream. */
 hat_status_t hat_mid_debug_dump(hat_mid_t* h, int32_t which, void* dst, void* hip_stream);
 
+/* ---- planner on its own (tests of the host logic, no GPU needed) ----------------------- */
+
+/* A handle without GPU memory and without any HIP call: it keeps the page and length state
+ * of hat_mid_create's handle and accepts hat_mid_debug_plan, hat_mid_kv_query,
+ * hat_mid_kv_compact (state only), hat_mid_release, hat_mid_last_error and hat_mid_destroy;
+ * the calls that need the GPU (forward, forward_host, kv_import, kv_export, step statistics,
+ * profiling, dumps) return HAT_EINVAL. */
+hat_status_t hat_mid_debug_create_host_only(const hat_mid_config_t* cfg, hat_mid_t** out);
+
+/* Validates and plans one step exactly as hat_mid_forward does -- same errors, same atomicity,
+ * page movements committed on success -- and returns the plan instead of running it.  Host
+ * arrays, any of which may be NULL: pos / kv_dst (cap_rows entries: each row's rotary position
+ * and page*16 + slot write target, in batch order), the chunk- and verify-attention work items
+ * (12 int32 words each: segment, first query row, query rows, first key, end key, first partial
+ * row or -1, segment start, first batch row, cache length, page-list offset, and for verify items
+ * two words of per-row visibility bytes) and the split-KV merge items (8 words: first batch row,
+ * rows, partial row of split 0, splits, partial rows between splits, 3 unused); cap_items bounds
+ * each item array.  The segments' hidden pointers are checked for NULL only. */
+hat_status_t hat_mid_debug_plan(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, int32_t* pos,
+                                int32_t* kv_dst, int32_t cap_rows, int32_t* chunk_items, int32_t* n_chunk_items,
+                                int32_t* verify_items, int32_t* n_verify_items, int32_t* merge_items,
+                                int32_t* n_merge_items, int32_t cap_items);
+
 /* ---- tuning aid ------------------------------------------------------------------ */
 
 /* Forces the tile shape and K split of one GEMM class in later forwards

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_forward_host", "hat_mid_release",
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_compact", "hat_mid_kv_import", "hat_mid_kv_export",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
-    "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_plan",
+    "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_plan", "hat_mid_debug_create_host_only", "hat_mid_debug_plan",
     "hat_sched_create", "hat_sched_destroy", "hat_sched_observe", "hat_sched_mu", "hat_sched_predict",
     "hat_sched_chunk_size", "hat_sched_parallel_draft_steps",
 ]
@@ -108,6 +108,11 @@ def load_library():
     lib.hat_mid_debug_gemm_tile_count.argtypes = []
     lib.hat_mid_debug_gemm_plan.restype = i32
     lib.hat_mid_debug_gemm_plan.argtypes = [i32, i32, i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+    lib.hat_mid_debug_create_host_only.restype = i32
+    lib.hat_mid_debug_create_host_only.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+    pi = C.POINTER(i32)
+    lib.hat_mid_debug_plan.restype = i32
+    lib.hat_mid_debug_plan.argtypes = [vp, C.POINTER(CSegment), i32, pi, pi, i32, pi, pi, pi, pi, pi, pi, i32]
     f64 = C.c_double
     lib.hat_sched_create.restype = i32
     lib.hat_sched_create.argtypes = [C.POINTER(i32), i32, f64, C.POINTER(vp)]
@@ -289,6 +294,81 @@ class HatMid:
 
     def gemm_tile_count(self):
         return int(self.lib.hat_mid_debug_gemm_tile_count())
+
+    def close(self):
+        if getattr(self, "_handle", None) is not None and self._handle.value:
+            self.lib.hat_mid_destroy(self._handle)
+            self._handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class HatPlanner:
+    """The host half of the library on its own (hat_mid_debug_create_host_only / hat_mid_debug_plan): validation,
+    page bookkeeping and the per-step plan, without a GPU.  For tests of the host logic."""
+
+    ATTN_FIELDS = ("seg", "q0", "nq", "kv_begin", "kv_end", "part_row", "start", "tok0", "kv_len", "pt_off", "vis_lo", "vis_hi")
+    MERGE_FIELDS = ("row0", "nrows", "part_row", "nsplit", "stride")
+
+    def __init__(self, cfg, n_pages, max_devices=64, max_step_tokens=8192, max_pos=16384):
+        self.lib = load_library()
+        self.max_step_tokens = max_step_tokens
+        self.ccfg = Config(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"],
+                           cfg["rms_eps"], cfg["rope_theta"], 16, n_pages, max_devices, max_step_tokens, max_pos, HAT_BF16)
+        self._handle = C.c_void_p()
+        rc = self.lib.hat_mid_debug_create_host_only(C.byref(self.ccfg), C.byref(self._handle))
+        if rc != 0:
+            raise HatError(rc, "hat_mid_debug_create_host_only failed")
+
+    def _check(self, rc):
+        if rc != 0:
+            raise HatError(rc, self.lib.hat_mid_last_error(self._handle).decode())
+
+    def plan(self, segments, cap_items=4096):
+        """segments: list of (device, kind, start, n) or (device, kind, start, n, tree masks).  Returns a dict with
+        pos, kv_dst (lists) and chunk_items / verify_items / merge_items (lists of dicts)."""
+        n = len(segments)
+        arr = (CSegment * max(n, 1))()
+        keep = []
+        rows = 0
+        for i, sg in enumerate(segments):
+            mask = None
+            if len(sg) > 4 and sg[4] is not None:
+                buf = (C.c_uint8 * len(sg[4]))(*[int(m) for m in sg[4]])
+                keep.append(buf)
+                mask = C.cast(buf, C.c_void_p)
+            arr[i] = CSegment(sg[0], sg[1], sg[3], sg[2], 1, 1, mask)   # hidden pointers: non-null placeholders
+            rows += max(int(sg[3]), 0)
+        cap_rows = max(rows, 1)
+        i32 = C.c_int32
+        pos, dst = (i32 * cap_rows)(), (i32 * cap_rows)()
+        ci, vi, mi = (i32 * (12 * cap_items))(), (i32 * (12 * cap_items))(), (i32 * (8 * cap_items))()
+        nc, nv, nm = i32(), i32(), i32()
+        self._check(self.lib.hat_mid_debug_plan(self._handle, arr, n, pos, dst, cap_rows, ci, C.byref(nc), vi, C.byref(nv),
+                                                mi, C.byref(nm), cap_items))
+        u32 = lambda x: x & 0xFFFFFFFF
+        items = lambda raw, cnt: [dict(zip(self.ATTN_FIELDS, [raw[12 * k + j] if j < 10 else u32(raw[12 * k + j]) for j in range(12)]))
+                                  for k in range(cnt)]
+        merges = [dict(zip(self.MERGE_FIELDS, [mi[8 * k + j] for j in range(5)])) for k in range(nm.value)]
+        return dict(pos=list(pos[:rows]), kv_dst=list(dst[:rows]), chunk_items=items(ci, nc.value),
+                    verify_items=items(vi, nv.value), merge_items=merges)
+
+    def release(self, device_id):
+        self._check(self.lib.hat_mid_release(self._handle, device_id))
+
+    def kv_compact(self, device_id, base_pos, keep):
+        arr = (C.c_int32 * max(len(keep), 1))(*[int(k) for k in keep])
+        self._check(self.lib.hat_mid_kv_compact(self._handle, device_id, base_pos, arr, len(keep), None))
+
+    def kv_query(self, device_id, cap=1 << 16):
+        ln, npg = C.c_int32(), C.c_int32()
+        buf = (C.c_int32 * cap)()
+        self._check(self.lib.hat_mid_kv_query(self._handle, device_id, C.byref(ln), buf, cap, C.byref(npg)))
+        return ln.value, list(buf[: npg.value])
 
     def close(self):
         if getattr(self, "_handle", None) is not None and self._handle.value:

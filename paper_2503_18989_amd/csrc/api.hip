@@ -178,6 +178,8 @@ struct hat_mid {
   bool slot_used[2] = {false, false};
   int host_slot = 0;
 
+  bool host_only = false;                  // built by hat_mid_debug_create_host_only: no GPU memory, no HIP calls
+  std::vector<int32_t> host_plan;          // its plan words
   int force_tile[4] = {-1, -1, -1, -1};   // tuning overrides per GEMM class (qkv, o, gate/up, down)
   int force_ksplit[4] = {0, 0, 0, 0};
 
@@ -360,6 +362,10 @@ static hat_status_t create_impl(const hat_mid_config_t* cfg, const hat_mid_layer
 
 void hat_mid_destroy(hat_mid_t* h) {
   if (!h) return;
+  if (h->host_only) {
+    delete h;
+    return;
+  }
   (void)hipDeviceSynchronize();
   for (int i = 0; i < kPlanBufs; ++i) {
     if (h->plan_host[i]) (void)hipHostFree(h->plan_host[i]);
@@ -413,8 +419,9 @@ hat_status_t hat_mid_kv_compact(hat_mid_t* h, int32_t device_id, int32_t base_po
     mv.dst[mv.n] = d.pages[dst >> 4] * 16 + (dst & 15);
     ++mv.n;
   }
-  HIP_TRY(h, hat_launch_kv_move(h->pool, h->layer_pool_elems, c.n_layers, c.n_pages, mv, c.n_heads, c.head_dim,
-                                (hipStream_t)hip_stream));
+  if (!h->host_only)
+    HIP_TRY(h, hat_launch_kv_move(h->pool, h->layer_pool_elems, c.n_layers, c.n_pages, mv, c.n_heads, c.head_dim,
+                                  (hipStream_t)hip_stream));
   d.len = base_pos + n_keep;
   const size_t want = (size_t)(d.len + 15) / 16;
   while (d.pages.size() > want) {
@@ -436,13 +443,22 @@ hat_status_t hat_mid_kv_query(const hat_mid_t* h, int32_t device_id, int32_t* kv
   return HAT_OK;
 }
 
-static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
-  if (!h) return HAT_EINVAL;
-  if (n_segs == 0) return HAT_OK;  // an empty step: no work, no state change
+// What the planning half of a step hands to the enqueueing half: where each array lies in the
+// plan words, and how many work items there are.
+struct StepPlan {
+  int T = 0, S = 0, n_append = 0;
+  size_t o_pos = 0, o_dst = 0, o_tseg = 0, o_toff = 0, o_sstart = 0, o_spt = 0, o_in = 0, o_out = 0, o_pt = 0, o_app = 0;
+  size_t o_ci = 0, o_vi = 0, o_mi = 0, words = 0;
+  int n_citems = 0, n_vitems = 0, n_mitems = 0;
+};
+
+// Host half of a step: validates every segment, commits the page movements, and writes the plan
+// (positions, write targets, page lists, attention work lists) into P (capacity: plan_words).
+// No GPU call: the same code serves the host-only handles that the planner's CPU tests use.
+static hat_status_t plan_step(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, int32_t* P, StepPlan* sp) {
   if (!segs || n_segs < 0) return fail(h, HAT_EINVAL, "no segments");
   const hat_mid_config_t& c = h->cfg;
   const Shapes& s = h->s;
-  hipStream_t st = (hipStream_t)hip_stream;
 
   // ---- validate everything before touching state
   if (n_segs > c.max_devices) return fail(h, HAT_EINVAL, "more segments (%d) than devices", n_segs);
@@ -501,11 +517,7 @@ static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, in
     np_total += (int)d.pages.size();
   }
 
-  // ---- plan blob
-  const int bi = h->plan_next;
-  h->plan_next = (h->plan_next + 1) % kPlanBufs;
-  if (h->plan_ev_used[bi]) HIP_TRY(h, hipEventSynchronize(h->plan_ev[bi]));
-  int32_t* P = h->plan_host[bi];
+  // ---- plan words
   size_t w = 0;
   auto take = [&](size_t n, size_t align_words) {
     w = align_up(w, align_words);
@@ -661,6 +673,34 @@ static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, in
   if (!vitems.empty()) memcpy(&P[o_vi], vitems.data(), vitems.size() * sizeof(HatAttnItem));
   if (!mitems.empty()) memcpy(&P[o_mi], mitems.data(), mitems.size() * sizeof(HatMergeItem));
 
+  sp->T = T; sp->S = S; sp->n_append = n_append;
+  sp->o_pos = o_pos; sp->o_dst = o_dst; sp->o_tseg = o_tseg; sp->o_toff = o_toff; sp->o_sstart = o_sstart;
+  sp->o_spt = o_spt; sp->o_in = o_in; sp->o_out = o_out; sp->o_pt = o_pt; sp->o_app = o_app;
+  sp->o_ci = o_ci; sp->o_vi = o_vi; sp->o_mi = o_mi; sp->words = w;
+  sp->n_citems = (int)citems.size(); sp->n_vitems = (int)vitems.size(); sp->n_mitems = (int)mitems.size();
+  return HAT_OK;
+}
+
+static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
+  if (!h) return HAT_EINVAL;
+  if (n_segs == 0) return HAT_OK;  // an empty step: no work, no state change
+  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle plans steps, it does not run them");
+  const hat_mid_config_t& c = h->cfg;
+  const Shapes& s = h->s;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // the pinned plan buffers rotate; this one was last read by the upload of three steps ago
+  const int bi = h->plan_next;
+  if (h->plan_ev_used[bi]) HIP_TRY(h, hipEventSynchronize(h->plan_ev[bi]));
+  int32_t* P = h->plan_host[bi];
+  StepPlan sp;
+  const hat_status_t prc = plan_step(h, segs, n_segs, P, &sp);
+  if (prc != HAT_OK) return prc;
+  h->plan_next = (bi + 1) % kPlanBufs;
+  const int T = sp.T, S = sp.S, n_append = sp.n_append;
+  const size_t o_pos = sp.o_pos, o_dst = sp.o_dst, o_tseg = sp.o_tseg, o_toff = sp.o_toff, o_sstart = sp.o_sstart;
+  const size_t o_spt = sp.o_spt, o_in = sp.o_in, o_out = sp.o_out, o_pt = sp.o_pt, o_app = sp.o_app;
+  const size_t o_ci = sp.o_ci, o_vi = sp.o_vi, o_mi = sp.o_mi, w = sp.words;
+
   // ---- enqueue
   HIP_TRY(h, hipEventRecord(h->ev_begin, st));
   HIP_TRY(h, hipMemcpyAsync(h->b.plan_dev, P, w * sizeof(int32_t), hipMemcpyHostToDevice, st));
@@ -703,16 +743,16 @@ static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, in
     HatAttn a{};
     a.qkv = h->b.qkv; a.pool_layer = pool_l; a.outP = h->b.attn; a.part_o = h->b.part_o; a.part_ml = h->b.part_ml;
     a.H = s.H; a.hd = s.hd; a.d = s.d; a.n_pages = c.n_pages;
-    if (!citems.empty()) {
-      a.items = (const HatAttnItem*)(D + o_ci); a.n_items = (int)citems.size();
+    if (sp.n_citems > 0) {
+      a.items = (const HatAttnItem*)(D + o_ci); a.n_items = sp.n_citems;
       LAUNCH(h, st, HAT_K_ATTN_CHUNK, hat_launch_attn_chunk(pd, a, st));
     }
-    if (!vitems.empty()) {
-      a.items = (const HatAttnItem*)(D + o_vi); a.n_items = (int)vitems.size();
+    if (sp.n_vitems > 0) {
+      a.items = (const HatAttnItem*)(D + o_vi); a.n_items = sp.n_vitems;
       LAUNCH(h, st, HAT_K_ATTN_VERIFY, hat_launch_attn_verify(pd, a, st));
     }
-    if (!mitems.empty())
-      LAUNCH(h, st, HAT_K_ATTN_MERGE, hat_launch_attn_merge(a, (const HatMergeItem*)(D + o_mi), (int)mitems.size(), st));
+    if (sp.n_mitems > 0)
+      LAUNCH(h, st, HAT_K_ATTN_MERGE, hat_launch_attn_merge(a, (const HatMergeItem*)(D + o_mi), sp.n_mitems, st));
     g = HatGemm{};
     g.W = ld.wo; g.X = h->b.attn; g.K = s.d; g.T = T; g.Nw = s.No; g.Nout = s.d; g.resid = h->b.resid;
     g.part = h->b.gemm_part; g.part_rows = s.gemm_part_rows;
@@ -774,6 +814,7 @@ hat_status_t hat_mid_last_step_stats(hat_mid_t* h, int32_t* tokens, float* gpu_m
 
 hat_status_t hat_mid_set_profiling(hat_mid_t* h, int32_t on) {
   if (!h) return HAT_EINVAL;
+  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle has no GPU side");
   h->profiling = on != 0;
   return HAT_OK;
 }
@@ -804,6 +845,7 @@ static hat_status_t fixture_pages(hat_mid_t* h, const DeviceState& d, int pos0, 
 
 static hat_status_t forward_host_impl(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
   if (!h) return HAT_EINVAL;
+  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle has no GPU side");
   if (n_segs == 0) return HAT_OK;
   if (!segs || n_segs < 0) return fail(h, HAT_EINVAL, "no segments");
   if (n_segs > h->cfg.max_devices) return fail(h, HAT_EINVAL, "more segments (%d) than devices", n_segs);
@@ -858,6 +900,7 @@ hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, i
 hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n, const void* k,
                                const void* v, void* hip_stream) {
   if (!h) return HAT_EINVAL;
+  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle has no GPU side");
   const hat_mid_config_t& c = h->cfg;
   if (device_id < 0 || device_id >= c.max_devices) return fail(h, HAT_EDEVICE, "device id %d out of range", device_id);
   if (layer < 0 || layer >= c.n_layers || n <= 0 || pos0 < 0 || !k || !v) return fail(h, HAT_EINVAL, "bad import arguments");
@@ -880,6 +923,7 @@ hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, i
 hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n, void* k,
                                void* v, void* hip_stream) {
   if (!h) return HAT_EINVAL;
+  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle has no GPU side");
   const hat_mid_config_t& c = h->cfg;
   if (device_id < 0 || device_id >= c.max_devices) return fail(h, HAT_EDEVICE, "device id %d out of range", device_id);
   if (layer < 0 || layer >= c.n_layers || n <= 0 || pos0 < 0 || !k || !v) return fail(h, HAT_EINVAL, "bad export arguments");
@@ -891,6 +935,58 @@ hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, i
   HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages, pos0, n,
                                   (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, st));
   return HAT_OK;
+}
+
+hat_status_t hat_mid_debug_create_host_only(const hat_mid_config_t* cfg, hat_mid_t** out) {
+  if (out) *out = nullptr;
+  if (!out || !valid_cfg(cfg)) return HAT_EINVAL;
+  try {
+    hat_mid* h = new hat_mid();
+    h->host_only = true;
+    h->cfg = *cfg;
+    h->s = make_shapes(*cfg);
+    h->pool = nullptr;
+    h->layer_pool_elems = (size_t)cfg->n_pages * kv_page_elems(cfg->n_heads, cfg->head_dim);
+    for (int i = 0; i < cfg->n_pages; ++i) h->free_pages.insert(i);
+    h->dev.resize(cfg->max_devices);
+    h->host_plan.resize(h->s.plan_words);
+    *out = h;
+    return HAT_OK;
+  } catch (...) {
+    return HAT_EHIP;
+  }
+}
+
+hat_status_t hat_mid_debug_plan(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, int32_t* pos,
+                                int32_t* kv_dst, int32_t cap_rows, int32_t* chunk_items, int32_t* n_chunk_items,
+                                int32_t* verify_items, int32_t* n_verify_items, int32_t* merge_items,
+                                int32_t* n_merge_items, int32_t cap_items) {
+  if (!h) return HAT_EINVAL;
+  if (!h->host_only) return fail(h, HAT_EINVAL, "hat_mid_debug_plan needs a host-only handle");
+  if (n_chunk_items) *n_chunk_items = 0;
+  if (n_verify_items) *n_verify_items = 0;
+  if (n_merge_items) *n_merge_items = 0;
+  if (n_segs == 0) return HAT_OK;
+  try {
+    StepPlan sp;
+    const int32_t* P = h->host_plan.data();
+    const hat_status_t rc = plan_step(h, segs, n_segs, h->host_plan.data(), &sp);
+    if (rc != HAT_OK) return rc;
+    if (sp.T > cap_rows || std::max(sp.n_citems, std::max(sp.n_vitems, sp.n_mitems)) > cap_items)
+      return fail(h, HAT_EINVAL, "output arrays too small for %d rows / %d, %d, %d items (the step has been planned)", sp.T,
+                  sp.n_citems, sp.n_vitems, sp.n_mitems);
+    if (pos) memcpy(pos, P + sp.o_pos, sp.T * sizeof(int32_t));
+    if (kv_dst) memcpy(kv_dst, P + sp.o_dst, sp.T * sizeof(int32_t));
+    if (chunk_items) memcpy(chunk_items, P + sp.o_ci, (size_t)sp.n_citems * sizeof(HatAttnItem));
+    if (verify_items) memcpy(verify_items, P + sp.o_vi, (size_t)sp.n_vitems * sizeof(HatAttnItem));
+    if (merge_items) memcpy(merge_items, P + sp.o_mi, (size_t)sp.n_mitems * sizeof(HatMergeItem));
+    if (n_chunk_items) *n_chunk_items = sp.n_citems;
+    if (n_verify_items) *n_verify_items = sp.n_vitems;
+    if (n_merge_items) *n_merge_items = sp.n_mitems;
+    return HAT_OK;
+  } catch (...) {
+    return fail(h, HAT_EHIP, "host allocation failed while planning the step");
+  }
 }
 
 hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile, int32_t ksplit) {
