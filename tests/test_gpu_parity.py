@@ -350,3 +350,18 @@ def test_randomized_schedules(cfg, seed):
         check(outs, refs)
         p.check_pages(range(ndev))
     p.close()
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(name="odd64", n_layers=2, d_model=192, n_heads=3, head_dim=64, d_ffn=500, rms_eps=1e-5, rope_theta=1e4),
+    dict(name="odd128", n_layers=2, d_model=384, n_heads=3, head_dim=128, d_ffn=1000, rms_eps=1e-6, rope_theta=5e5),
+], ids=["3x64", "3x128"])
+def test_widths_that_are_not_multiples_of_the_tiles(cfg):
+    # d_model = 192 / 384 (weight rows padded to 256-row panels), FFN widths 500 / 1000 (not multiples of
+    # 64: padded k for the down projection), an odd head count, another rotary base
+    p = Pair(cfg, 71, n_pages=64, max_devices=4, max_step_tokens=512, max_pos=512)
+    check(*p.step([(0, hi.CHUNK, 0, 77), (1, hi.CHUNK, 0, 300)]))
+    check(*p.step([(0, hi.VERIFY, 77, 5), (1, hi.VERIFY, 300, 8, hi.tree_masks(hi.MEDUSA_LIKE_TREE)), (2, hi.CHUNK, 0, 33)]))
+    check(*p.step([(0, hi.VERIFY, 79, 8), (2, hi.CHUNK, 33, 130)]))
+    p.check_pages(range(4))
+    p.close()
