@@ -280,3 +280,24 @@ def test_cfg5_13b_last_chunk_of_each_size(chunk):
     e = check(to_np(outs[3]), y, "chunk %d" % chunk)
     print("cfg5 chunk %d: rel err %.3e" % (chunk, e))
     gpu.close()
+
+
+def test_widest_model_the_library_accepts():
+    """d_model = 8192 (64 heads x 128), the upper limit of the configuration check: one layer, a 70-row
+    chunk, then a chain and a tree over it."""
+    import torch
+    from oracle import OracleMiddle
+    from paper_2503_18989_amd import Segment
+    cfg = dict(name="wide", n_layers=1, d_model=8192, n_heads=64, head_dim=128, d_ffn=2048, rms_eps=1e-6, rope_theta=1e4)
+    seed = 6000
+    gpu, weights = build(cfg, seed, n_pages=32, max_devices=2, max_step_tokens=128, max_pos=256)
+    ref = OracleMiddle(cfg, weights)
+    x0 = hi.hidden_rows(70, 8192, seed, 0); x1 = hi.hidden_rows(8, 8192, seed, 1); x2 = hi.hidden_rows(5, 8192, seed, 2)
+    steps = [[(0, hi.CHUNK, 0, x0, None)], [(0, hi.VERIFY, 70, x1, hi.tree_masks(hi.MEDUSA_LIKE_TREE))], [(0, hi.VERIFY, 70, x2, None)]]
+    for st in steps:
+        outs = gpu.forward([Segment(d, k, s, to_dev_bf16(x), tree_mask=m) for d, k, s, x, m in st])
+        torch.cuda.synchronize()
+        refs = ref.forward([(d, s, x, m) for d, k, s, x, m in st])
+        for o, r in zip(outs, refs):
+            check(to_np(o), r, "d_model 8192")
+    gpu.close()
