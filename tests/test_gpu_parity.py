@@ -365,3 +365,22 @@ def test_widths_that_are_not_multiples_of_the_tiles(cfg):
     check(*p.step([(0, hi.VERIFY, 79, 8), (2, hi.CHUNK, 33, 130)]))
     p.check_pages(range(4))
     p.close()
+
+
+def test_positions_beyond_twenty_thousand():
+    # a 20 000-row cache installed by import, then a 200-row chunk, a chain and a tree at positions
+    # 20 000+: rotary angles of thousands of radians, a page list of 1 260 entries, 300+ key stages
+    import torch
+    cfg = dict(SMALL128, n_layers=1)
+    H, hd = cfg["n_heads"], cfg["head_dim"]
+    p = Pair(cfg, 81, n_pages=2 * 20320 // 16 + 8, max_devices=2, max_step_tokens=256, max_pos=20400)
+    for dev in (0, 1):
+        k, v = hi.kv_prefix(20000, H, hd, 81, dev, 0)
+        p.gpu.kv_import(dev, 0, 0, to_dev_bf16(k).view(-1, H, hd), to_dev_bf16(v).view(-1, H, hd))
+        p.ref.import_kv(dev, 0, 0, k, v)
+        for q in range(0, 20000, 250):                      # the page model takes the prefix in steps it accepts
+            p.pages.step([(dev, hi.CHUNK, q, 250)])
+    check(*p.step([(0, hi.CHUNK, 20000, 200), (1, hi.VERIFY, 20000, 8, hi.tree_masks(hi.MEDUSA_LIKE_TREE))]))
+    check(*p.step([(0, hi.VERIFY, 20200, 5), (1, hi.VERIFY, 20001, 8)]))
+    p.check_pages([0, 1])
+    p.close()
