@@ -384,3 +384,31 @@ def test_positions_beyond_twenty_thousand():
     check(*p.step([(0, hi.VERIFY, 20200, 5), (1, hi.VERIFY, 20001, 8)]))
     p.check_pages([0, 1])
     p.close()
+
+
+def test_sixty_four_devices_in_one_step():
+    # as many segments as the handle has devices, of every kind, in one step -- twice, the second time
+    # with every device continuing, rolling back or restarting
+    rng = np.random.default_rng(5)
+    p = Pair(SMALL64, 82, n_pages=64 * 6, max_devices=64, max_step_tokens=1024, max_pos=96)
+    segs = []
+    for d in range(64):
+        segs.append((d, hi.CHUNK, 0, int(rng.integers(1, 17))) if d % 3 else (d, hi.VERIFY, 0, int(rng.integers(1, 9))))
+    check(*p.step(segs))
+    p.check_pages(range(64))
+    ln = {sg[0]: sg[3] for sg in segs}
+    segs2 = []
+    for d in map(int, rng.permutation(64)):
+        r = d % 4
+        if r == 0:
+            n = int(rng.integers(1, 9)); tr = hi.random_tree(82, n, d)
+            segs2.append((d, hi.VERIFY, ln[d], n, hi.tree_masks(tr)))
+        elif r == 1:
+            segs2.append((d, hi.VERIFY, max(ln[d] - 2, 0), 5))
+        elif r == 2:
+            segs2.append((d, hi.CHUNK, ln[d], 9))
+        else:
+            segs2.append((d, hi.CHUNK, 0, 12))              # starts over: rollback to nothing
+    check(*p.step(segs2))
+    p.check_pages(range(64))
+    p.close()
