@@ -412,3 +412,22 @@ def test_sixty_four_devices_in_one_step():
     check(*p.step(segs2))
     p.check_pages(range(64))
     p.close()
+
+
+def test_results_are_bitwise_reproducible():
+    # split-K and split-KV reductions run in a fixed order (no atomics): two handles given the same
+    # steps -- long enough for both kinds of split -- return the same bits
+    import torch
+    from paper_2503_18989_amd import Segment
+    outs = []
+    for _ in range(2):
+        p = Pair(SMALL128, 83, n_pages=200, max_devices=4, max_step_tokens=1280, max_pos=2048)
+        xs = [to_dev_bf16(hi.hidden_rows(n, 512, 83, i)) for i, n in enumerate((900, 300, 8, 5))]
+        a = p.gpu.forward([Segment(0, hi.CHUNK, 0, xs[0]), Segment(1, hi.CHUNK, 0, xs[1])])
+        b = p.gpu.forward([Segment(0, hi.VERIFY, 900, xs[2], tree_mask=hi.tree_masks(hi.MEDUSA_LIKE_TREE)),
+                           Segment(1, hi.VERIFY, 298, xs[3])])
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in a + b])
+        p.close()
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
