@@ -182,13 +182,30 @@ def profile_classes(m, run_steps):
     return {k: (ms / 1e3 / max(cnt, 1), cnt) for k, (ms, cnt) in t.items() if cnt}
 
 
+def timed_steps(step, n):
+    """Mean GPU milliseconds of n consecutive calls of step(), between two events on the current stream."""
+    import torch
+    st = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(st)
+    for _ in range(n):
+        step()
+    e1.record(st)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
 # ---------------------------------------------------------------- legs for the attention kernels
-def attention_legs(cfg7, dev_layers, n_layers=2):
-    """Chunk-attention MFMA fraction (mixed batch, config-3 shape) and verify-attention HBM GB/s
-    (config-4 shape: 30 devices, 5 draft rows each, cache lengths uniform in [1024, 8192])."""
+def attention_legs(cfg7, dev_layers):
+    """The verify-heavy step (config-4 shape: 30 devices, 5 draft rows each, cache lengths uniform in
+    [1024, 8192]), the same devices submitting trees of 8, and the mixed step (config-3 shape: 10 chunks
+    + 20 verify segments over prefixes U[256, 4096]), each at the model's full depth: step time,
+    per-class kernel times, verify-attention HBM GB/s, chunk-attention and GEMM MFMA fractions."""
     import torch
     from paper_2503_18989_amd import HatMid, Segment
-    cfg = hi.with_layers(cfg7, n_layers)
+    cfg = dict(cfg7)
+    n_layers = cfg["n_layers"]
     d, H, hd = cfg["d_model"], cfg["n_heads"], cfg["head_dim"]
     out = {}
     kbig = (torch.randn((8192, H, hd), device="cuda", dtype=torch.float32) * 1.28).to(torch.bfloat16)
@@ -216,11 +233,12 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
     sec = prof["attn_verify"][0]
     out["verify_attn"] = dict(roof(fl, by, sec), us_per_launch=sec * 1e6, algorithmic_bytes=by,
                               traffic=recorded_leg_traffic("attn_verify_kernel<128>"),
+                              traffic_source="profiles/traffic_attention_legs.txt (recorded rocprofv3 --pmc runs, not measured in this run)",
                               workload="30 devices x 5 rows, cache lengths U[1024,8192], 7B-shaped layer")
     out["verify_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
-    tok, ms = m.last_step_stats()
-    out["verify_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms,
-                          "hidden_tokens_per_s_extrapolated_to_30_layers": tok / (ms * 1e-3 / n_layers * 30)}
+    ms = timed_steps(vstep, 8)
+    out["verify_step"] = {"tokens": 150, "layers": n_layers, "gpu_ms": ms, "hidden_tokens_per_s": 150 / (ms * 1e-3),
+                          "roofline": out["verify_attn"]}
 
     # --- the same devices submitting a tree of 8 candidates each (the tree-verifying comparison
     # system's step, Sec. 4.1) instead of a chain of 5: what the larger step costs on this engine
@@ -234,12 +252,11 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
     prof_t = profile_classes(m, lambda: [tstep() for _ in range(8)])
     fl, by = attn_work([(ln, 8) for ln in lengths], d)
     sec = prof_t["attn_verify"][0]
-    tok_t, ms_t = m.last_step_stats()
+    ms_t = timed_steps(tstep, 8)
     out["tree_verify_attn"] = dict(roof(fl, by, sec), us_per_launch=sec * 1e6, algorithmic_bytes=by,
                                    workload="30 devices x tree of 8, same caches")
-    out["tree_verify_step"] = {"tokens": tok_t, "gpu_ms_for_%d_layers" % n_layers: ms_t,
-                               "hidden_tokens_per_s_extrapolated_to_30_layers": tok_t / (ms_t * 1e-3 / n_layers * 30),
-                               "ms_ratio_to_chain_of_5": ms_t / ms}
+    out["tree_verify_step"] = {"tokens": 240, "layers": n_layers, "gpu_ms": ms_t, "hidden_tokens_per_s": 240 / (ms_t * 1e-3),
+                               "ms_ratio_to_chain_of_5": ms_t / ms, "roofline": out["tree_verify_attn"]}
     m.close()
     del m
     torch.cuda.empty_cache()
@@ -268,9 +285,11 @@ def attention_legs(cfg7, dev_layers, n_layers=2):
     gw = gemm_work(T, d, cfg["d_ffn"])
     out["mixed_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
     out["mixed_step_gemm_mfma_frac"] = {k: gw[k][0] / prof[k][0] / PEAK_MFMA_BF16 for k in gw}
-    tok, ms = m.last_step_stats()
-    out["mixed_step"] = {"tokens": tok, "gpu_ms_for_%d_layers" % n_layers: ms,
-                         "hidden_tokens_per_s_extrapolated_to_30_layers": tok / (ms * 1e-3 / n_layers * 30)}
+    ms = timed_steps(mstep, 8)
+    dom = max(gw, key=lambda k: prof[k][0])
+    out["mixed_step"] = {"tokens": T, "layers": n_layers, "gpu_ms": ms, "hidden_tokens_per_s": T / (ms * 1e-3),
+                         "roofline": dict(roof(gw[dom][0], gw[dom][1], prof[dom][0]), kernel=dom,
+                                          us_per_launch=prof[dom][0] * 1e6)}
     m.close()
     return out
 
@@ -482,7 +501,9 @@ def main():
     per_step = {k: v["us_per_launch"] * v["launches_per_step"] for k, v in kernels.items()}
     dom = max((k for k in per_step if "bound" in kernels[k]), key=lambda k: per_step[k])
     roofline = {k: kernels[dom][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
-    roofline.update(kernel=dom, traffic=recorded_traffic(dom), us_per_launch=kernels[dom]["us_per_launch"],
+    roofline.update(kernel=dom, traffic=recorded_traffic(dom),
+                    traffic_source="profiles/traffic_cfg2.txt (recorded rocprofv3 --pmc runs of this workload, not measured in this run)",
+                    us_per_launch=kernels[dom]["us_per_launch"],
                     algorithmic_bytes=gw[dom][1] if dom in gw else None,
                     algorithmic_flops=gw[dom][0] if dom in gw else None)
     # whole-step roofline: sum over classes of max(flop/peak, bytes/peak), matrix kernels only

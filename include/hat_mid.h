@@ -22,7 +22,13 @@
  * fp16 operands (activations are produced in fp16, saturating; bf16 weights and
  * cache rows are widened to fp16, exact for magnitudes in [2^-17, 65504]) and
  * accumulate in fp32; softmax, normalisation, rotary embedding, SiLU and the
- * residual stream are fp32.
+ * residual stream are fp32.  Supported activation range: every intermediate that
+ * feeds a matrix product (norm outputs, q/k/v, attention outputs, the SwiGLU
+ * product) is converted to fp16 with saturation, so a magnitude above 65504 is
+ * clamped to +-65504 (never infinity, no error raised); results are exact to the
+ * stated tolerance only while those intermediates stay below that bound, which
+ * holds by orders of magnitude for unit-scale hidden states and trained LLaMA
+ * weights.  The fp32 residual stream itself is not clamped.
  *
  * Conventions
  *  - "device pointer" = address in GPU memory (HBM) of the current HIP device;
@@ -43,7 +49,13 @@
  *    returns a hat_status_t (or a size / pointer), and hat_mid_last_error gives
  *    the text of the last failure on the handle.
  *  - hat_mid_forward validates every segment and the page demand of the whole
- *    step before it changes anything: on error no KV row, page or length moves.
+ *    step before it changes anything: on a validation error (HAT_EINVAL,
+ *    HAT_ENOMEM, HAT_EPOS, HAT_EDUP, HAT_EDEVICE) no KV row, page or length
+ *    moves.  If a HIP runtime call fails while the step is being enqueued
+ *    (HAT_EHIP), lengths and page lists are put back as they were before the
+ *    call, but kernels already enqueued may still run: cache rows at or beyond
+ *    the start positions of that step's segments are then unspecified, and the
+ *    caller should regard the stream as failed.
  */
 #ifndef HAT_MID_H
 #define HAT_MID_H
@@ -177,7 +189,8 @@ hat_status_t hat_mid_kv_compact(hat_mid_t* h, int32_t device_id, int32_t base_po
  * the pool, its length becomes 0.  Unknown-but-valid ids are a no-op. */
 hat_status_t hat_mid_release(hat_mid_t* h, int32_t device_id);
 
-/* Frees host-side state (pinned staging, events).  GPU buffers stay with the caller. */
+/* Frees host-side state (pinned staging, events) after waiting for the handle's own work: its
+ * internal copy stream and the stream of its most recent call.  GPU buffers stay with the caller. */
 void hat_mid_destroy(hat_mid_t* h);
 
 /* Text of the last error on this handle ("" if none); valid until the next call. */
@@ -289,6 +302,18 @@ hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile,
  * planner.  Returns HAT_EINVAL on a null pointer. */
 hat_status_t hat_mid_debug_gemm_plan(int32_t T, int32_t Nw, int32_t Nout, int32_t K, int32_t epilogue,
                                      int32_t part_rows, int32_t* tile, int32_t* ksplit);
+
+/* Workgroup counts that the attention work lists aim for (chunk kernel, verify kernel): long key
+ * ranges are split over several workgroups until a launch has about that many.  0 keeps a value.
+ * For tests that force the split and unsplit paths, and for sweeps; the work-list capacities were
+ * sized at create time, so a larger target splits only as far as they allow.  Results change only
+ * in fp32 summation order. */
+hat_status_t hat_mid_debug_set_attn_targets(hat_mid_t* h, int32_t chunk_target, int32_t verify_target);
+
+/* Lowers the capacity (in 32-bit words) that a step's plan may occupy; 0 restores the real one.
+ * Lets a test reach the "plan exceeds capacity" failure, which happens after the step's page
+ * movements, and check that they are undone. */
+hat_status_t hat_mid_debug_limit_plan(hat_mid_t* h, int64_t max_words);
 
 /* Number of entries in the library's GEMM tile table (valid `tile` values of
  * hat_mid_debug_force_gemm are 0 .. count-1).  No GPU work. */

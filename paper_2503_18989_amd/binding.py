@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = [
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_compact", "hat_mid_kv_import", "hat_mid_kv_export",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
     "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_plan", "hat_mid_debug_create_host_only", "hat_mid_debug_plan",
+    "hat_mid_debug_set_attn_targets", "hat_mid_debug_limit_plan",
     "hat_sched_create", "hat_sched_destroy", "hat_sched_observe", "hat_sched_mu", "hat_sched_predict",
     "hat_sched_chunk_size", "hat_sched_parallel_draft_steps",
 ]
@@ -110,6 +111,10 @@ def load_library():
     lib.hat_mid_debug_gemm_plan.argtypes = [i32, i32, i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.hat_mid_debug_create_host_only.restype = i32
     lib.hat_mid_debug_create_host_only.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+    lib.hat_mid_debug_set_attn_targets.restype = i32
+    lib.hat_mid_debug_set_attn_targets.argtypes = [vp, i32, i32]
+    lib.hat_mid_debug_limit_plan.restype = i32
+    lib.hat_mid_debug_limit_plan.argtypes = [vp, C.c_int64]
     pi = C.POINTER(i32)
     lib.hat_mid_debug_plan.restype = i32
     lib.hat_mid_debug_plan.argtypes = [vp, C.POINTER(CSegment), i32, pi, pi, i32, pi, pi, pi, pi, pi, pi, i32]
@@ -231,7 +236,9 @@ class HatMid:
             outs.append(out)
             arr[i] = CSegment(s.device_id, s.kind, x.shape[0], s.start_pos, x.data_ptr(), out.data_ptr(),
                               self._mask_ptr(s, keep))
-        self._keep_host = (segments, outs)   # the copies are asynchronous
+        # the copies are asynchronous and two calls may be in flight (the upload of this one runs
+        # while the previous step computes): hold the host tensors of the last two calls
+        self._keep_host = (getattr(self, "_keep_host", [None, None]) + [(segments, outs)])[-2:]
         self._check(self.lib.hat_mid_forward_host(self._handle, arr, n, self._stream(stream)))
         return outs
 
@@ -294,6 +301,9 @@ class HatMid:
 
     def gemm_tile_count(self):
         return int(self.lib.hat_mid_debug_gemm_tile_count())
+
+    def set_attn_targets(self, chunk_target=0, verify_target=0):
+        self._check(self.lib.hat_mid_debug_set_attn_targets(self._handle, chunk_target, verify_target))
 
     def close(self):
         if getattr(self, "_handle", None) is not None and self._handle.value:
@@ -359,6 +369,12 @@ class HatPlanner:
 
     def release(self, device_id):
         self._check(self.lib.hat_mid_release(self._handle, device_id))
+
+    def limit_plan(self, max_words):
+        self._check(self.lib.hat_mid_debug_limit_plan(self._handle, int(max_words)))
+
+    def set_attn_targets(self, chunk_target=0, verify_target=0):
+        self._check(self.lib.hat_mid_debug_set_attn_targets(self._handle, chunk_target, verify_target))
 
     def kv_compact(self, device_id, base_pos, keep):
         arr = (C.c_int32 * max(len(keep), 1))(*[int(k) for k in keep])

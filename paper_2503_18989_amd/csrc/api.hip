@@ -23,6 +23,8 @@ namespace {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
 
+constexpr int kCapAttnTarget = 2048;  // workgroup target that the work-list capacities are sized for
+
 struct LayerDev {
   act_t *wqkv, *wo, *wgu, *wd;
   float *g_attn, *g_ffn;
@@ -63,9 +65,9 @@ Shapes make_shapes(const hat_mid_config_t& c) {
   s.Tcap = round_up(c.max_step_tokens, 256);
   s.attn_target = 256;  // one 8-wave workgroup per CU
   s.verify_target = 2048;
-  if (const char* e = getenv("HAT_ATTN_TARGET")) s.attn_target = s.verify_target = std::max(1, atoi(e));
-  if (const char* e = getenv("HAT_VERIFY_TARGET")) s.verify_target = std::max(1, atoi(e));
-  const int per_head = (std::max(s.attn_target, s.verify_target) + s.H - 1) / s.H;
+  // capacities are sized for this target; a larger one (hat_mid_debug_set_attn_targets) splits
+  // only as far as they allow -- the planner checks every capacity before it splits
+  const int per_head = (kCapAttnTarget + s.H - 1) / s.H;
   s.chunk_items_cap = 2 * per_head + s.Tcap / 128 + c.max_devices + 2;
   s.verify_items_cap = 2 * per_head + c.max_devices + 2;
   s.merge_cap = s.Tcap / 16 + s.Tcap / 128 + 2 * c.max_devices + 2;
@@ -178,6 +180,17 @@ struct hat_mid {
   bool slot_used[2] = {false, false};
   int host_slot = 0;
 
+  // what the step being planned has done to the page state, so that a failure after the pages
+  // moved (plan capacity, a HIP call while enqueueing) can put everything back
+  struct PageOp { int32_t page; bool taken; };   // taken: the page left the free set; else it entered it
+  std::vector<PageOp> undo_pages;
+  std::vector<std::pair<int32_t, DeviceState>> undo_dev;
+  bool undo_on = false;
+
+  hipStream_t last_stream = nullptr;       // stream of the most recent enqueue (hat_mid_destroy waits for it)
+  bool used_stream = false;
+  size_t plan_limit = 0;                   // > 0: lowered plan capacity (hat_mid_debug_limit_plan)
+
   bool host_only = false;                  // built by hat_mid_debug_create_host_only: no GPU memory, no HIP calls
   std::vector<int32_t> host_plan;          // its plan words
   int force_tile[4] = {-1, -1, -1, -1};   // tuning overrides per GEMM class (qkv, o, gate/up, down)
@@ -223,7 +236,42 @@ int32_t take_lowest(hat_mid* h) {
   auto it = h->free_pages.begin();
   int32_t id = *it;
   h->free_pages.erase(it);
+  if (h->undo_on) h->undo_pages.push_back({id, true});
   return id;
+}
+
+void give_back(hat_mid* h, int32_t id) {
+  h->free_pages.insert(id);
+  if (h->undo_on) h->undo_pages.push_back({id, false});
+}
+
+// Page movements of one call are logged between undo_begin and undo_commit; undo_rollback puts
+// lengths, page lists and the free set back to what they were at undo_begin.
+void undo_begin(hat_mid* h) {
+  h->undo_pages.clear();
+  h->undo_dev.clear();
+  h->undo_on = true;
+}
+void undo_save_device(hat_mid* h, int32_t id) { h->undo_dev.emplace_back(id, h->dev[id]); }
+void undo_commit(hat_mid* h) {
+  h->undo_on = false;
+  h->undo_pages.clear();
+  h->undo_dev.clear();
+}
+void undo_rollback(hat_mid* h) {
+  h->undo_on = false;
+  for (auto it = h->undo_pages.rbegin(); it != h->undo_pages.rend(); ++it) {
+    if (it->taken) h->free_pages.insert(it->page);
+    else h->free_pages.erase(it->page);
+  }
+  for (auto it = h->undo_dev.rbegin(); it != h->undo_dev.rend(); ++it) h->dev[it->first] = std::move(it->second);
+  h->undo_pages.clear();
+  h->undo_dev.clear();
+}
+
+void note_stream(hat_mid* h, hipStream_t st) {
+  h->last_stream = st;
+  h->used_stream = true;
 }
 
 hipEvent_t get_event(hat_mid* h) {
@@ -310,7 +358,6 @@ static hat_status_t create_impl(const hat_mid_config_t* cfg, const hat_mid_layer
   };
   hipError_t e;
   if ((e = hat_gemm_init()) != hipSuccess) return bail(e, "gemm init");
-  if ((e = hat_attn_init()) != hipSuccess) return bail(e, "attention init");
   for (int i = 0; i < kPlanBufs; ++i) {
     if ((e = hipHostMalloc((void**)&h->plan_host[i], h->s.plan_words * sizeof(int32_t), hipHostMallocDefault)) !=
         hipSuccess)
@@ -356,6 +403,7 @@ static hat_status_t create_impl(const hat_mid_config_t* cfg, const hat_mid_layer
     if ((e = hat_launch_bf16_to_f32((const bf16_t*)w.ffn_norm, ld.g_ffn, s.d, st)) != hipSuccess)
       return bail(e, "gain");
   }
+  note_stream(h, st);
   *out = h;
   return HAT_OK;
 }
@@ -366,7 +414,10 @@ void hat_mid_destroy(hat_mid_t* h) {
     delete h;
     return;
   }
-  (void)hipDeviceSynchronize();
+  // wait for this handle's work only: its copy stream and the stream of its last enqueue (calls on
+  // one handle are stream-ordered, so that covers all of them)
+  if (h->copy_stream) (void)hipStreamSynchronize(h->copy_stream);
+  if (h->used_stream) (void)hipStreamSynchronize(h->last_stream);
   for (int i = 0; i < kPlanBufs; ++i) {
     if (h->plan_host[i]) (void)hipHostFree(h->plan_host[i]);
     if (h->plan_ev[i]) (void)hipEventDestroy(h->plan_ev[i]);
@@ -419,6 +470,7 @@ hat_status_t hat_mid_kv_compact(hat_mid_t* h, int32_t device_id, int32_t base_po
     mv.dst[mv.n] = d.pages[dst >> 4] * 16 + (dst & 15);
     ++mv.n;
   }
+  if (!h->host_only) note_stream(h, (hipStream_t)hip_stream);
   if (!h->host_only)
     HIP_TRY(h, hat_launch_kv_move(h->pool, h->layer_pool_elems, c.n_layers, c.n_pages, mv, c.n_heads, c.head_dim,
                                   (hipStream_t)hip_stream));
@@ -497,12 +549,15 @@ static hat_status_t plan_step(hat_mid_t* h, const hat_mid_segment_t* segs, int32
     if (need > free_after) return fail(h, HAT_ENOMEM, "KV pool exhausted: need %ld pages, %ld free", need, free_after);
   }
 
-  // ---- commit the page movements: all rollbacks, then all allocations
+  // ---- move the pages: all rollbacks, then all allocations.  Logged: the caller commits the
+  // step once it has been planned and enqueued, and rolls it back otherwise.
+  undo_begin(h);
+  for (int i = 0; i < n_segs; ++i) undo_save_device(h, segs[i].device_id);
   for (int i = 0; i < n_segs; ++i) {
     DeviceState& d = h->dev[segs[i].device_id];
     const size_t keep = (size_t)(segs[i].start_pos + 15) / 16;
     while (d.pages.size() > keep) {
-      h->free_pages.insert(d.pages.back());
+      give_back(h, d.pages.back());
       d.pages.pop_back();
     }
     d.len = segs[i].start_pos;
@@ -667,7 +722,11 @@ static hat_status_t plan_step(hat_mid_t* h, const hat_mid_segment_t* segs, int32
     std::stable_sort(vitems.begin(), vitems.end(), by_cost);
   }
   const size_t o_ci = take(12 * citems.size(), 4), o_vi = take(12 * vitems.size(), 4), o_mi = take(8 * mitems.size(), 8);
-  if (w > s.plan_words) return fail(h, HAT_EINVAL, "internal: plan of %zu words exceeds capacity %zu", w, s.plan_words);
+  const size_t plan_cap = h->plan_limit ? std::min(h->plan_limit, s.plan_words) : s.plan_words;
+  if (w > plan_cap) {
+    undo_rollback(h);
+    return fail(h, HAT_EINVAL, "internal: plan of %zu words exceeds capacity %zu", w, plan_cap);
+  }
   static_assert(sizeof(HatAttnItem) == 48 && sizeof(HatMergeItem) == 32, "plan item sizes");
   if (!citems.empty()) memcpy(&P[o_ci], citems.data(), citems.size() * sizeof(HatAttnItem));
   if (!vitems.empty()) memcpy(&P[o_vi], vitems.data(), vitems.size() * sizeof(HatAttnItem));
@@ -681,27 +740,15 @@ static hat_status_t plan_step(hat_mid_t* h, const hat_mid_segment_t* segs, int32
   return HAT_OK;
 }
 
-static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
-  if (!h) return HAT_EINVAL;
-  if (n_segs == 0) return HAT_OK;  // an empty step: no work, no state change
-  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle plans steps, it does not run them");
+// Device half of a step: uploads the plan and enqueues the kernels of every layer on st.
+static hat_status_t enqueue_step(hat_mid_t* h, const StepPlan& sp, const int32_t* P, int bi, hipStream_t st) {
   const hat_mid_config_t& c = h->cfg;
   const Shapes& s = h->s;
-  hipStream_t st = (hipStream_t)hip_stream;
-  // the pinned plan buffers rotate; this one was last read by the upload of three steps ago
-  const int bi = h->plan_next;
-  if (h->plan_ev_used[bi]) HIP_TRY(h, hipEventSynchronize(h->plan_ev[bi]));
-  int32_t* P = h->plan_host[bi];
-  StepPlan sp;
-  const hat_status_t prc = plan_step(h, segs, n_segs, P, &sp);
-  if (prc != HAT_OK) return prc;
-  h->plan_next = (bi + 1) % kPlanBufs;
   const int T = sp.T, S = sp.S, n_append = sp.n_append;
   const size_t o_pos = sp.o_pos, o_dst = sp.o_dst, o_tseg = sp.o_tseg, o_toff = sp.o_toff, o_sstart = sp.o_sstart;
   const size_t o_spt = sp.o_spt, o_in = sp.o_in, o_out = sp.o_out, o_pt = sp.o_pt, o_app = sp.o_app;
   const size_t o_ci = sp.o_ci, o_vi = sp.o_vi, o_mi = sp.o_mi, w = sp.words;
 
-  // ---- enqueue
   HIP_TRY(h, hipEventRecord(h->ev_begin, st));
   HIP_TRY(h, hipMemcpyAsync(h->b.plan_dev, P, w * sizeof(int32_t), hipMemcpyHostToDevice, st));
   HIP_TRY(h, hipEventRecord(h->plan_ev[bi], st));
@@ -781,6 +828,31 @@ static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, in
   return HAT_OK;
 }
 
+static hat_status_t forward_impl(hat_mid_t* h, const hat_mid_segment_t* segs, int32_t n_segs, void* hip_stream) {
+  if (!h) return HAT_EINVAL;
+  if (n_segs == 0) return HAT_OK;  // an empty step: no work, no state change
+  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle plans steps, it does not run them");
+  hipStream_t st = (hipStream_t)hip_stream;
+  // the pinned plan buffers rotate; this one was last read by the upload of three steps ago
+  const int bi = h->plan_next;
+  if (h->plan_ev_used[bi]) HIP_TRY(h, hipEventSynchronize(h->plan_ev[bi]));
+  int32_t* P = h->plan_host[bi];
+  StepPlan sp;
+  const hat_status_t prc = plan_step(h, segs, n_segs, P, &sp);
+  if (prc != HAT_OK) return prc;   // nothing moved (plan_step undoes its own page movements)
+  note_stream(h, st);
+  const hat_status_t erc = enqueue_step(h, sp, P, bi, st);
+  if (erc != HAT_OK) {
+    // a HIP call failed part-way: lengths and pages go back to where they were; kernels already
+    // enqueued may still write cache rows at or beyond the segments' start positions
+    undo_rollback(h);
+    return erc;
+  }
+  undo_commit(h);
+  h->plan_next = (bi + 1) % kPlanBufs;
+  return HAT_OK;
+}
+
 // No exception crosses the ABI: the entry points that allocate host memory (vectors, the handle)
 // turn an allocation failure into a status.
 hat_status_t hat_mid_create(const hat_mid_config_t* cfg, const hat_mid_layer_weights_t* layers, void* kv_pool,
@@ -797,6 +869,7 @@ hat_status_t hat_mid_forward(hat_mid_t* h, const hat_mid_segment_t* segs, int32_
   try {
     return forward_impl(h, segs, n_segs, hip_stream);
   } catch (...) {
+    if (h && h->undo_on) undo_rollback(h);
     return fail(h, HAT_EHIP, "host allocation failed while planning the step");
   }
 }
@@ -893,6 +966,7 @@ hat_status_t hat_mid_forward_host(hat_mid_t* h, const hat_mid_segment_t* segs, i
   try {
     return forward_host_impl(h, segs, n_segs, hip_stream);
   } catch (...) {
+    if (h && h->undo_on) undo_rollback(h);
     return fail(h, HAT_EHIP, "host allocation failed while planning the step");
   }
 }
@@ -910,13 +984,23 @@ hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, i
   const size_t want = (size_t)(pos0 + n + 15) / 16;
   if (want > d.pages.size() && want - d.pages.size() > h->free_pages.size())
     return fail(h, HAT_ENOMEM, "KV pool exhausted on import");
+  undo_begin(h);
+  undo_save_device(h, device_id);
   while (d.pages.size() < want) d.pages.push_back(take_lowest(h));
   d.len = std::max(d.len, pos0 + n);
   hipStream_t st = (hipStream_t)hip_stream;
+  note_stream(h, st);
   hat_status_t rc = fixture_pages(h, d, pos0, n, st);
-  if (rc != HAT_OK) return rc;
-  HIP_TRY(h, hat_launch_kv_import(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages, pos0, n,
-                                  (const bf16_t*)k, (const bf16_t*)v, c.n_heads, c.head_dim, st));
+  if (rc == HAT_OK) {
+    const hipError_t e = hat_launch_kv_import(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages,
+                                              pos0, n, (const bf16_t*)k, (const bf16_t*)v, c.n_heads, c.head_dim, st);
+    if (e != hipSuccess) rc = fail(h, HAT_EHIP, "kv import launch failed: %s", hipGetErrorString(e));
+  }
+  if (rc != HAT_OK) {
+    undo_rollback(h);   // the pages taken for this import return to the pool, the length is as before
+    return rc;
+  }
+  undo_commit(h);
   return HAT_OK;
 }
 
@@ -930,6 +1014,7 @@ hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, i
   const DeviceState& d = h->dev[device_id];
   if (pos0 + n > d.len) return fail(h, HAT_EPOS, "export of rows %d..%d beyond cache length %d", pos0, pos0 + n, d.len);
   hipStream_t st = (hipStream_t)hip_stream;
+  note_stream(h, st);
   hat_status_t rc = fixture_pages(h, d, pos0, n, st);
   if (rc != HAT_OK) return rc;
   HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages, pos0, n,
@@ -972,6 +1057,7 @@ hat_status_t hat_mid_debug_plan(hat_mid_t* h, const hat_mid_segment_t* segs, int
     const int32_t* P = h->host_plan.data();
     const hat_status_t rc = plan_step(h, segs, n_segs, h->host_plan.data(), &sp);
     if (rc != HAT_OK) return rc;
+    undo_commit(h);
     if (sp.T > cap_rows || std::max(sp.n_citems, std::max(sp.n_vitems, sp.n_mitems)) > cap_items)
       return fail(h, HAT_EINVAL, "output arrays too small for %d rows / %d, %d, %d items (the step has been planned)", sp.T,
                   sp.n_citems, sp.n_vitems, sp.n_mitems);
@@ -985,6 +1071,7 @@ hat_status_t hat_mid_debug_plan(hat_mid_t* h, const hat_mid_segment_t* segs, int
     if (n_merge_items) *n_merge_items = sp.n_mitems;
     return HAT_OK;
   } catch (...) {
+    if (h->undo_on) undo_rollback(h);
     return fail(h, HAT_EHIP, "host allocation failed while planning the step");
   }
 }
@@ -997,6 +1084,19 @@ hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile,
 }
 
 int32_t hat_mid_debug_gemm_tile_count(void) { return hat_gemm_tile_count(); }
+
+hat_status_t hat_mid_debug_set_attn_targets(hat_mid_t* h, int32_t chunk_target, int32_t verify_target) {
+  if (!h || chunk_target < 0 || verify_target < 0) return HAT_EINVAL;
+  if (chunk_target > 0) h->s.attn_target = chunk_target;
+  if (verify_target > 0) h->s.verify_target = verify_target;
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_debug_limit_plan(hat_mid_t* h, int64_t max_words) {
+  if (!h || max_words < 0) return HAT_EINVAL;
+  h->plan_limit = (size_t)max_words;
+  return HAT_OK;
+}
 
 hat_status_t hat_mid_debug_gemm_plan(int32_t T, int32_t Nw, int32_t Nout, int32_t K, int32_t epilogue,
                                      int32_t part_rows, int32_t* tile, int32_t* ksplit) {

@@ -661,8 +661,6 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(HatAttn a, const HatMer
 
 }  // namespace
 
-hipError_t hat_attn_init() { return hipSuccess; }
-
 hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStream_t st) {
   if (a.n_items <= 0) return hipSuccess;
   dim3 grid(a.n_items, a.H);

@@ -15,7 +15,7 @@ constexpr int HAT_CHUNK_QROWS = 256;
 
 // ---- GEMM: out[t, f] = sum_k X[t, k] * W[f, k], operands in P32 layout ------
 enum HatEpilogue {
-  HAT_EPI_P32 = 0,     // bf16 result, P32 layout, row length Nout
+  HAT_EPI_P32 = 0,     // fp16 (act_t) result, P32 layout, row length Nout
   HAT_EPI_SWIGLU = 1,  // W rows interleaved (16 gate, 16 up): silu(gate)*up, P32, row length Nout
   HAT_EPI_RESID = 2    // resid[t, f] += result  (fp32 row-major, leading dim Nout)
 };
@@ -47,7 +47,8 @@ hipError_t hat_gemm_init();  // one-time function attributes (dynamic LDS size)
 // ---- weight re-tiling (create time) -----------------------------------------
 // dst: P32 [Nw, Kd] in act_t (bf16 -> fp16 is exact for |w| in [2^-17, 65504]).  mode 0: row R <- src0[R] (R < n0), else 0.
 // mode 1 (qkv): rows [0,n0) <- src0, [n0,2n0) <- src1, [2n0,3n0) <- src2.
-// mode 2 (gate/up): row R: blk=R/64, w=R%64; f = 32*blk + w%32; (w<32 ? src0 : src1)[f], zero if f >= n0.
+// mode 2 (gate/up): row R: blk=R/32, w=R%32; f = 16*blk + w%16; (w<16 ? src0 : src1)[f], zero if f >= n0
+// (every 32-row block = 16 gate rows followed by the up rows of the same 16 features).
 // Source rows have Ks elements (Ks <= Kd; columns beyond Ks are zero).
 hipError_t hat_launch_retile(act_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1,
                              const bf16_t* src2, int n0, int Ks, int mode, hipStream_t st);
@@ -83,7 +84,7 @@ hipError_t hat_launch_scatter(const HatPlanDev& p, const float* resid, const flo
                               int io_dtype, hipStream_t st);
 hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, float2* table, int half, hipStream_t st);
 // x = resid + sum of nparts partial sums (part[i][t][:], stride T*d); if nparts > 0 the sum is
-// written back to resid.  out = rmsnorm(x) * gain as bf16 in P32 layout.
+// written back to resid.  out = rmsnorm(x) * gain as fp16 (act_t) in P32 layout.
 hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, act_t* outP, int T,
                               int d, float eps, hipStream_t st);
 // qkv: P32 [., 3d]; rotates q in place, writes rotated k and v into the pool of one layer
@@ -131,7 +132,6 @@ struct HatAttn {
 hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStream_t st);
 hipError_t hat_launch_attn_verify(const HatPlanDev& p, const HatAttn& a, hipStream_t st);
 hipError_t hat_launch_attn_merge(const HatAttn& a, const HatMergeItem* items, int n_items, hipStream_t st);
-hipError_t hat_attn_init();
 
 // ---- fixtures ------------------------------------------------------------------
 // k, v: [n, H, hd] bf16 plain; pages: device array of the page ids covering the rows

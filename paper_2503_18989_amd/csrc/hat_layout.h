@@ -1,7 +1,7 @@
 // Memory layouts shared by all kernels of the middle-submodel forward.
 //
-// (1) "P32" operand layout.  Every GEMM operand -- re-tiled weights and all bf16
-//     activations -- is stored as panels of 32 rows; inside a panel the unit is
+// (1) "P32" operand layout.  Every GEMM operand -- re-tiled weights and all
+//     activations, both fp16 (act_t) -- is stored as panels of 32 rows; inside a panel the unit is
 //     an "octet" (8 consecutive k elements of one row, 16 bytes) and octets are
 //     ordered [k/8][row%32].  A lane of a 64-wide wavefront that needs MFMA
 //     32x32x16 operand rows (lane%32) and k-octet (lane/32) therefore reads

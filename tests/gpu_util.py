@@ -16,6 +16,48 @@ def rel_l2(got, ref):
     return float(np.linalg.norm(np.asarray(got, np.float64) - ref) / max(np.linalg.norm(ref), 1e-30))
 
 
+def added_err(got, ref, x_in):
+    """max |got - ref| / max |ref - x_in|: the error measured against what the layers ADDED to the
+    residual stream.  With unit-scale inputs and N(0, 0.02^2) weights a shallow stack changes its input
+    by a few per cent only, so rel_err (normalised by max |ref|) hides kernel errors there; this one
+    does not.  Meaningful with fp32 I/O: a bf16 output carries a rounding of about 2e-3 * max |ref|."""
+    ref = np.asarray(ref, np.float64)
+    x_in = np.asarray(x_in, np.float64)
+    return float(np.max(np.abs(np.asarray(got, np.float64) - ref)) / max(np.max(np.abs(ref - x_in)), 1e-30))
+
+
+def tol_for_depth(n_layers):
+    """Parity bar on rel_err: 2e-2 is the bar of the full-depth workloads (30 / 38 layers, where the
+    error has been amplified about 9x on its way through random-init layers); a stack of at most 3
+    layers with bf16 output sits near the output rounding (2e-3) and is held to 6e-3, so that an error
+    of kernel size cannot pass."""
+    return 6e-3 if n_layers <= 3 else 2e-2
+
+
+def progress(msg):
+    """One line to gpurun_out/test_progress.log (pytest captures stdout; long tests report here)."""
+    import os
+    import time
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    try:
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write("%s %s\n" % (time.strftime("%H:%M:%S"), msg))
+    except OSError:
+        pass
+    print(msg, flush=True)
+
+
+def report(what, got, ref, x_in=None):
+    """Prints (and logs) the error figures of one comparison; returns rel_err."""
+    e = rel_err(got, ref)
+    line = "%s: rel %.3e, l2 %.3e" % (what, e, rel_l2(got, ref))
+    if x_in is not None:
+        line += ", vs added %.3e" % added_err(got, ref, x_in)
+    progress(line)
+    return e
+
+
 def to_dev_bf16(x):
     import torch
     return torch.from_numpy(hi.bf16_bits(np.ascontiguousarray(x, np.float32)).view(np.int16)).view(torch.bfloat16).cuda()
@@ -56,6 +98,7 @@ class Pair:
             x = inputs[i] if inputs is not None else hi.hidden_rows(n, self.cfg["d_model"], self.seed, self.counter, dev)
             xs.append(x)
         self.counter += 1
+        self.last_inputs = xs
         gsegs = []
         for (dev, kind, start, n), x, m in zip(segs, xs, masks):
             xd = to_dev_bf16(x) if self.io_dtype == "bf16" else torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()
@@ -64,7 +107,13 @@ class Pair:
         torch.cuda.synchronize()
         refs = self.ref.forward([(dev, start, x, m) for (dev, kind, start, n), x, m in zip(segs, xs, masks)])
         self.pages.step(segs)
-        return [to_np(o) for o in outs], refs
+        outs = [to_np(o) for o in outs]
+        # figures of this step, worst segment: error against max |ref| and against what the layers added
+        self.last_rel = max(rel_err(o, r) for o, r in zip(outs, refs))
+        self.last_added = max(added_err(o, r, x) for o, r, x in zip(outs, refs, xs))
+        self.worst_rel = max(getattr(self, "worst_rel", 0.0), self.last_rel)
+        self.worst_added = max(getattr(self, "worst_added", 0.0), self.last_added)
+        return outs, refs
 
     def compact(self, dev, base, keep):
         """Keeps tree nodes `keep` of the step that started at `base`, on all three sides."""
@@ -79,4 +128,7 @@ class Pair:
             assert self.gpu.kv_query(d) == self.pages.query(d), "page table of device %d differs" % d
 
     def close(self):
+        if hasattr(self, "worst_rel"):
+            progress("%s (%d layers, %s io): worst rel %.3e, worst vs added %.3e"
+                     % (self.cfg.get("name", "?"), self.cfg["n_layers"], self.io_dtype, self.worst_rel, self.worst_added))
         self.gpu.close()

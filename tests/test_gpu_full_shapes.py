@@ -6,15 +6,19 @@ width, or a subset of the devices of a step (segments never interact, so the
 oracle may follow any subset while the GPU processes the whole batch) -- or
 (b) checks a property that holds at any size (chunk-split invariance at full
 depth, integer page state against the page model at every step).
-Tolerance as elsewhere: max|gpu - ref| / max|ref| <= 2e-2 per segment."""
+Tolerance: max|gpu - ref| / max|ref| per segment <= 2e-2 at full depth (30 layers) and <= 6e-3 for
+the 1- and 2-layer models (gpu_util.tol_for_depth: a shallow stack sits near the bf16 output rounding,
+so the full-depth bar would let a kernel-sized error pass there).  The same workloads at their full
+depth are in test_gpu_depth.py."""
 import numpy as np
 import pytest
 
 import hat_inputs as hi
-from gpu_util import rel_err, rel_l2, to_dev_bf16, to_np, dev_weights
+from gpu_util import added_err, progress, rel_err, rel_l2, to_dev_bf16, to_np, dev_weights, tol_for_depth
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2
+TOL = 2e-2                      # full depth
+TOL_SHALLOW = tol_for_depth(2)  # 1- and 2-layer models
 
 
 def build(cfg, seed, n_pages, weights=None, **kw):
@@ -35,45 +39,11 @@ def device_random_kv(n, H, hd, seed):
     return k, v
 
 
-def check(o, r, what=""):
+def check(o, r, what="", tol=TOL_SHALLOW):
     assert np.all(np.isfinite(o)), what
     e = rel_err(o, r)
-    assert e <= TOL, "%s rel err %.3e (l2 %.3e)" % (what, e, rel_l2(o, r))
+    assert e <= tol, "%s rel err %.3e (l2 %.3e)" % (what, e, rel_l2(o, r))
     return e
-
-
-def test_cfg2_7b_full_depth_first_chunk_and_split_invariance():
-    """30 layers, d 4096: the oracle follows the first 256-row chunk through all
-    30 layers; the whole 2048-row prompt is then checked GPU-vs-GPU between the
-    benchmark's 8x256 split and a 4x512 split (chunked prefill is a re-scheduling)."""
-    import torch
-    from oracle import OracleMiddle
-    from paper_2503_18989_amd import Segment
-    cfg = hi.MID7B
-    seed = 2000
-    gpu, weights = build(cfg, seed, n_pages=2 * 2048 // 16 + 8, max_devices=4, max_step_tokens=512, max_pos=2048)
-    xs = [hi.hidden_rows(256, cfg["d_model"], seed, i) for i in range(8)]
-    outs = []
-    for i, x in enumerate(xs):
-        outs.append(to_np(gpu.forward([Segment(0, hi.CHUNK, 256 * i, to_dev_bf16(x))])[0]))
-    torch.cuda.synchronize()
-    ref = OracleMiddle(cfg, lambda l: weights[l])
-    y0 = ref.forward([(0, 0, xs[0])])[0]
-    e = check(outs[0], y0, "chunk 0 through 30 layers")
-    print("cfg2 full depth: rel err %.3e, l2 %.3e" % (e, rel_l2(outs[0], y0)))
-    # K/V of the last layer for the first chunk
-    k, v = gpu.kv_export(0, cfg["n_layers"] - 1, 0, 256)
-    assert rel_err(to_np(k), ref.kv[0][-1][0]) < TOL and rel_err(to_np(v), ref.kv[0][-1][1]) < TOL
-    # a different split of the same prompt on a second device
-    xall = np.concatenate(xs)
-    outs2 = []
-    for i in range(4):
-        outs2.append(to_np(gpu.forward([Segment(1, hi.CHUNK, 512 * i, to_dev_bf16(xall[512 * i:512 * (i + 1)]))])[0]))
-    torch.cuda.synchronize()
-    a, b = np.concatenate(outs), np.concatenate(outs2)
-    assert rel_err(a, b) <= TOL / 2, "8x256 vs 4x512 differ by %.3e" % rel_err(a, b)
-    assert gpu.kv_query(0)[0] == 2048 and gpu.kv_query(1)[0] == 2048
-    gpu.close()
 
 
 def test_cfg2_7b_two_layers_all_chunks():
@@ -95,7 +65,7 @@ def test_cfg2_7b_two_layers_all_chunks():
         worst = max(worst, check(y, ref.forward([(dev, start, x)])[0], "chunk %d" % i))
         pm.step(step)
         assert gpu.kv_query(0) == pm.query(0)
-    print("cfg2 2 layers: worst rel err %.3e" % worst)
+    progress("cfg2 2 layers: worst rel err %.3e" % worst)
     gpu.close()
 
 
@@ -141,7 +111,7 @@ def test_cfg3_7b_mixed_step_sampled_devices():
     worst = max(check(o, r, "device") for o, r in zip(got, refs))
     for o in outs:
         assert torch.isfinite(o.float()).all()
-    print("cfg3: T=%d, sampled %d segments, worst rel err %.3e" % (T, len(refs), worst))
+    progress("cfg3 2 layers: T=%d, sampled %d segments, worst rel err %.3e" % (T, len(refs), worst))
     gpu.close()
 
 
@@ -186,7 +156,7 @@ def test_cfg4_7b_verify_heavy_64_steps_with_rollback():
         got = [to_np(o) for s, o in zip(step, outs) if s[0] in sampled]
         for o, r in zip(got, refs):
             worst = max(worst, check(o, r, "step %d" % it))
-    print("cfg4: 64 steps, worst rel err %.3e" % worst)
+    progress("cfg4 2 layers: 64 steps, worst rel err %.3e" % worst)
     gpu.close()
 
 
@@ -243,7 +213,7 @@ def test_tree_decoding_7b_30_devices_16_steps():
         torch.cuda.synchronize()
         for dev in range(30):
             assert gpu.kv_query(dev) == pm.query(dev), "step %d device %d" % (it, dev)
-    print("tree decoding: %d steps, worst rel err %.3e" % (steps, worst))
+    progress("tree decoding 2 layers: %d steps, worst rel err %.3e" % (steps, worst))
     gpu.close()
 
 
@@ -278,7 +248,7 @@ def test_cfg5_13b_last_chunk_of_each_size(chunk):
         assert gpu.kv_query(dev)[0] == 8192 and torch.isfinite(outs[dev].float()).all()
     y = ref.forward([(3, start, xs[3])])[0]
     e = check(to_np(outs[3]), y, "chunk %d" % chunk)
-    print("cfg5 chunk %d: rel err %.3e" % (chunk, e))
+    progress("cfg5 2 layers, chunk %d: rel err %.3e" % (chunk, e))
     gpu.close()
 
 

@@ -1,18 +1,24 @@
 """GPU parity: the HIP library against the CPU oracle on the same seeded inputs.
 
-Bar: max|gpu - ref| / max|ref| <= 2e-2 per segment on output hidden states (bf16-valued
-weights and cache, fp16 MFMA operands, fp32 accumulation, fp32 residual stream); page ids, slots and cache
-lengths bit-exact against the integer page model."""
+Bar on output hidden states (bf16-valued weights and cache, fp16 MFMA operands, fp32 accumulation,
+fp32 residual stream): max|gpu - ref| / max|ref| per segment.  The workloads' 2e-2 is stated for the
+full 30/38-layer stack (tests/test_gpu_depth.py); every model in this file has at most 3 layers, where
+the error is a fraction of that, so the bar here is 6e-3 (bf16 output rounding alone is about 2e-3),
+and the fp32-I/O cases are also held to 6e-3 of what the layers ADDED to their input
+(max|gpu - ref| / max|ref - x|), which is what exposes an error of kernel size.  Every Pair logs both
+figures.  Page ids, slots and cache lengths are bit-exact against the integer page model."""
 import os
 
 import numpy as np
 import pytest
 
 import hat_inputs as hi
-from gpu_util import Pair, rel_err, rel_l2, to_dev_bf16, to_np
+from gpu_util import Pair, added_err, progress, rel_err, rel_l2, to_dev_bf16, to_np
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2
+TOL = 6e-3     # every model here has at most 3 layers: the depth-appropriate bar (gpu_util.tol_for_depth)
+# fp32 I/O only: error against what the layers added to their input, max|gpu - ref| / max|ref - x|
+ADDED_TOL = 6e-3    # measured 1.4e-3 .. 2.4e-3 (fp16 operand and bf16 cache roundings)
 
 SMALL64 = dict(name="small64", n_layers=3, d_model=256, n_heads=4, head_dim=64, d_ffn=688, rms_eps=1e-6, rope_theta=1e4)
 SMALL128 = dict(name="small128", n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ffn=1408, rms_eps=1e-5, rope_theta=1e4)
@@ -112,21 +118,45 @@ def test_ragged_row_counts_cover_every_gemm_tile(T):
 def test_every_gemm_tile_forced(T):
     # every entry of the tile table on every GEMM class, with and without a K split where the
     # class allows one; the weight rows (768 / 512 / 1536 / 256 after padding) are not multiples
-    # of the 96- and 192-row tiles, so their ragged last feature tile is covered as well
-    p = Pair(SMALL64, 12, n_pages=64, max_devices=2, max_step_tokens=512, max_pos=1024)
-    x = hi.hidden_rows(T, 256, 12, 0, 0)
+    # of the 96- and 192-row tiles, so their ragged last feature tile is covered as well.
+    # One layer, fp32 I/O: per forced tile the outputs of the QKV product (rotated q), of the
+    # gate/up product (SwiGLU activation) and of the two accumulating products (the output rows,
+    # measured against what the layer added) are each compared with the oracle's stage.
+    from oracle import decoder as od
+    from paper_2503_18989_amd import Segment
+    import torch
+    cfg = dict(SMALL64, n_layers=1)
+    d, H, hd = cfg["d_model"], cfg["n_heads"], cfg["head_dim"]
+    p = Pair(cfg, 12, n_pages=64, io_dtype="f32", max_devices=2, max_step_tokens=512, max_pos=1024)
+    x = hi.hidden_rows(T, d, 12, 0, 0)
     ref = p.ref.forward([(0, 0, x)])[0]
-    xd = to_dev_bf16(x)
+    w = {k: v.astype(np.float64) for k, v in p.weights[0].items()}
+    x64 = x.astype(np.float64)
+    xn = od.rmsnorm(x64, w["attn_norm"], cfg["rms_eps"])
+    q = od.rope_rotate_half((xn @ w["wq"].T).reshape(T, H, hd), np.arange(T), cfg["rope_theta"]).reshape(T, d)
+    K, V = p.ref.kv[0][0]
+    hmid = x64 + od.prefix_causal_attention(q.reshape(T, H, hd), K, V, 0).reshape(T, d) @ w["wo"].T
+    xn2 = od.rmsnorm(hmid, w["ffn_norm"], cfg["rms_eps"])
+    act = od.silu(xn2 @ w["w_gate"].T) * (xn2 @ w["w_up"].T)
+    xd = torch.from_numpy(x).cuda()
     n_tiles = p.gpu.gemm_tile_count()
     assert n_tiles >= 10
-    from paper_2503_18989_amd import Segment
+    worst = {"q": 0.0, "act": 0.0, "out": 0.0, "added": 0.0}
     for tile in range(n_tiles):
         for ks in (1, 2):
             for which in range(4):
                 p.gpu.force_gemm(which, tile, ks)
             out = to_np(p.gpu.forward([Segment(0, hi.CHUNK, 0, xd)])[0])
-            e = rel_err(out, ref)
-            assert np.all(np.isfinite(out)) and e <= TOL, "tile %d ksplit %d: rel err %.3e" % (tile, ks, e)
+            eq = rel_err(to_np(p.gpu.debug_dump("q", T)), q)
+            ea = rel_err(to_np(p.gpu.debug_dump("act", T)), act)
+            e, eadd = rel_err(out, ref), added_err(out, ref, x)
+            for k, v in (("q", eq), ("act", ea), ("out", e), ("added", eadd)):
+                worst[k] = max(worst[k], v)
+            assert np.all(np.isfinite(out)), "tile %d ksplit %d" % (tile, ks)
+            assert eq <= TOL and ea <= TOL and e <= TOL and eadd <= ADDED_TOL, \
+                "tile %d ksplit %d: q %.3e, act %.3e, out %.3e, out vs added %.3e" % (tile, ks, eq, ea, e, eadd)
+    progress("forced tiles, T=%d: worst q %.3e, act %.3e, out %.3e, out vs added %.3e"
+             % (T, worst["q"], worst["act"], worst["out"], worst["added"]))
     p.close()
 
 
@@ -150,12 +180,12 @@ def test_mixed_ragged_batches_with_rollback(cfg):
     p.close()
 
 
-@pytest.mark.parametrize("target", ["64", "4096"])
-def test_split_kv_paths_long_cache(target, monkeypatch):
+@pytest.mark.parametrize("target", [64, 4096])
+def test_split_kv_paths_long_cache(target):
     # a large work-group target forces the key range of both attention kernels to be
     # split over several work-groups and merged; a small one keeps them whole
-    monkeypatch.setenv("HAT_ATTN_TARGET", target)
     p = Pair(SMALL128, 31, n_pages=160, max_devices=4, max_step_tokens=2048, max_pos=4096)
+    p.gpu.set_attn_targets(target, target)
     outs, refs = p.step([(0, hi.CHUNK, 0, 700), (1, hi.CHUNK, 0, 1000)])
     check(outs, refs)
     outs, refs = p.step([(0, hi.VERIFY, 700, 5), (1, hi.CHUNK, 1000, 143)])
@@ -173,11 +203,13 @@ def test_chunked_equals_unchunked_on_gpu_and_f32_io():
     a = Pair(cfg, 41, n_pages=64, io_dtype="f32", max_devices=2, max_step_tokens=512, max_pos=1024)
     outs_a, refs_a = a.step([(0, hi.CHUNK, 0, 200)], inputs=[x])
     check(outs_a, refs_a)
+    assert a.last_added <= ADDED_TOL, "error against what the 3 layers added: %.3e" % a.last_added
     b = Pair(cfg, 41, n_pages=64, io_dtype="f32", max_devices=2, max_step_tokens=512, max_pos=1024)
     got = []
     for s, n in ((0, 17), (17, 64), (81, 100), (181, 19)):
         o, r = b.step([(0, hi.CHUNK, s, n)], inputs=[x[s:s + n]])
         check(o, r)
+        assert b.last_added <= ADDED_TOL
         got.append(o[0])
     assert rel_err(np.concatenate(got), outs_a[0]) < 1.5e-2
     a.close(); b.close()
@@ -431,3 +463,51 @@ def test_results_are_bitwise_reproducible():
         p.close()
     for x, y in zip(*outs):
         assert torch.equal(x, y)
+
+
+def test_activations_beyond_the_fp16_range_saturate():
+    # Matrix-product operands are fp16 with a saturating conversion: a SwiGLU product beyond 65504 is
+    # clamped to +-65504 (never infinity).  Gate / up weights scaled by 512 / 256 (powers of two: still bf16
+    # values) push a few products of a 1-layer model past the bound.  Pinned: the clamped elements read
+    # exactly +-65504, every other activation element matches the oracle, rows without a clamped
+    # element match at the usual bar, and every output is finite.
+    from oracle import decoder as od
+    from paper_2503_18989_amd import Segment
+    import torch
+    cfg = dict(SMALL64, n_layers=1)
+    d, T = cfg["d_model"], 120
+    p = Pair(cfg, 97, n_pages=32, gain_jitter=0.0, io_dtype="f32", max_devices=2, max_step_tokens=128, max_pos=256)
+    w = dict(p.weights[0])
+    w["w_gate"] = w["w_gate"] * np.float32(512); w["w_up"] = w["w_up"] * np.float32(256)
+    p.gpu.close()
+    from gpu_util import dev_weights
+    from paper_2503_18989_amd import HatMid
+    from oracle import OracleMiddle
+    p.gpu = HatMid(cfg, [dev_weights(w)], n_pages=32, io_dtype="f32", max_devices=2, max_step_tokens=128, max_pos=256)
+    p.ref = OracleMiddle(cfg, [w])
+    x = hi.hidden_rows(T, d, 97, 0)
+    out = to_np(p.gpu.forward([Segment(0, hi.CHUNK, 0, torch.from_numpy(x).cuda())])[0])
+    ref = p.ref.forward([(0, 0, x)])[0]
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    x64 = x.astype(np.float64)
+    H, hd = cfg["n_heads"], cfg["head_dim"]
+    xn = od.rmsnorm(x64, w64["attn_norm"], cfg["rms_eps"])
+    q = od.rope_rotate_half((xn @ w64["wq"].T).reshape(T, H, hd), np.arange(T), cfg["rope_theta"])
+    K, V = p.ref.kv[0][0]
+    hmid = x64 + od.prefix_causal_attention(q, K, V, 0).reshape(T, d) @ w64["wo"].T
+    xn2 = od.rmsnorm(hmid, w64["ffn_norm"], cfg["rms_eps"])
+    act = od.silu(xn2 @ w64["w_gate"].T) * (xn2 @ w64["w_up"].T)
+    got = to_np(p.gpu.debug_dump("act", T))
+    sat = np.abs(act) > 65504 * 1.01
+    near = (np.abs(act) > 65504 * 0.99) & ~sat
+    assert sat.sum() >= 3, "the inputs were meant to exceed the fp16 range (%d do)" % sat.sum()
+    assert np.all(np.isfinite(got)) and np.all(np.isfinite(out))
+    assert np.array_equal(got[sat], np.sign(act[sat]) * 65504.0)
+    inside = ~sat & ~near
+    assert np.max(np.abs(got[inside] - act[inside])) / np.max(np.abs(act[inside])) < 3e-3
+    clean = ~np.any(sat | near, axis=1)
+    assert clean.sum() >= 10
+    assert rel_err(out[clean], ref[clean]) <= TOL
+    progress("fp16 saturation: %d of %d SwiGLU products clamped, %d clean rows at %.3e, clamped rows at %.3e"
+             % (sat.sum(), sat.size, clean.sum(), rel_err(out[clean], ref[clean]), rel_err(out[~clean], ref[~clean])))
+    p.gpu.close()

@@ -10,7 +10,7 @@ import hat_inputs as hi
 from gpu_util import Pair, rel_err, rel_l2, to_dev_bf16, to_np
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2
+TOL = 6e-3     # every model here has at most 3 layers: the depth-appropriate bar (gpu_util.tol_for_depth)
 
 SMALL64 = dict(name="small64", n_layers=3, d_model=256, n_heads=4, head_dim=64, d_ffn=688, rms_eps=1e-6, rope_theta=1e4)
 SMALL128 = dict(name="small128", n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ffn=1408, rms_eps=1e-5, rope_theta=1e4)
@@ -68,10 +68,10 @@ def test_tree_steps_compaction_and_what_follows(cfg):
     p.close()
 
 
-@pytest.mark.parametrize("target", ["64", "4096"])
-def test_tree_over_a_long_cache_split_and_whole(target, monkeypatch):
-    monkeypatch.setenv("HAT_ATTN_TARGET", target)
+@pytest.mark.parametrize("target", [64, 4096])
+def test_tree_over_a_long_cache_split_and_whole(target):
     p = Pair(SMALL128, 42, n_pages=160, max_devices=4, max_step_tokens=2048, max_pos=4096)
+    p.gpu.set_attn_targets(target, target)
     check(*p.step([(0, hi.CHUNK, 0, 1500), (1, hi.CHUNK, 0, 333)]))
     check(*p.step([(0, hi.VERIFY, 1500, 8, tree(hi.MEDUSA_LIKE_TREE)), (1, hi.VERIFY, 333, 8, tree(hi.random_tree(9, 8)))]))
     p.compact(0, 1500, hi.tree_path(hi.MEDUSA_LIKE_TREE, 5)); p.compact(1, 333, [])

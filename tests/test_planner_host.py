@@ -193,3 +193,36 @@ def test_benchmark_shaped_steps_fit_every_capacity(which):
     disjoint(part_rows)
     assert [lib.kv_query(sg[0]) for sg in segs] == [pm.query(sg[0]) for sg in segs]
     lib.close()
+
+
+def test_plan_capacity_failure_undoes_the_page_movements():
+    # the "plan exceeds capacity" failure is only found after the step's rollbacks and allocations have
+    # been made: every length, page list and the free set must come back exactly, and the handle must
+    # carry on as if the failed call had never happened (compared with a planner that never saw it)
+    a, pm = both(64, max_devices=4, max_step_tokens=256, max_pos=512)
+    b = HatPlanner(SHAPE, 64, max_devices=4, max_step_tokens=256, max_pos=512)
+    first = [(0, hi.CHUNK, 0, 100), (1, hi.CHUNK, 0, 40), (2, hi.CHUNK, 0, 33)]
+    for h in (a, b):
+        h.plan(first)
+    pm.step(first)
+    snap = [a.kv_query(d) for d in range(4)]
+    # rolls device 0 back over three pages, extends device 1, restarts device 2, admits device 3
+    step = [(0, hi.VERIFY, 60, 5), (1, hi.CHUNK, 40, 100), (2, hi.CHUNK, 0, 20), (3, hi.CHUNK, 0, 50)]
+    a.limit_plan(8)
+    with pytest.raises(HatError) as e:
+        a.plan(step)
+    assert e.value.code == -1 and "capacity" in str(e.value)
+    assert [a.kv_query(d) for d in range(4)] == snap
+    a.limit_plan(0)
+    pa, pb = a.plan(step), b.plan(step)
+    pm.step(step)
+    assert pa == pb
+    for d in range(4):
+        assert a.kv_query(d) == b.kv_query(d) == pm.query(d)
+    # the free set is intact as well: the next allocations take the same lowest ids on both
+    nxt = [(3, hi.CHUNK, 50, 200), (0, hi.VERIFY, 65, 8)]
+    assert a.plan(nxt) == b.plan(nxt)
+    pm.step(nxt)
+    for d in range(4):
+        assert a.kv_query(d) == b.kv_query(d) == pm.query(d)
+    a.close(); b.close()
