@@ -217,6 +217,22 @@ hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, i
 hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n,
                                void* k, void* v, void* hip_stream);
 
+/* hat_mid_kv_export for callers that may not allocate or synchronise: serving loops that move a
+ * device's cache elsewhere (migration, snapshots) from code where hipMalloc is forbidden -- under
+ * stream capture, inside tight step loops, in harnesses that ban it.  Same arguments, checks and
+ * results as hat_mid_kv_export, but the page ids of the exported rows are staged in an array
+ * that the library holds statically on every GPU (16 KB per GPU, for the life of the process)
+ * instead of in the workspace, they travel there with an asynchronous copy from a pinned buffer
+ * made at create time, and nothing waits for the stream: the call makes no hipMalloc / hipFree,
+ * no allocating library call and no stream synchronisation (it waits, on the host, only for the
+ * previous call's upload of page ids to have left the pinned buffer).
+ * Limit: rows pos0 .. pos0+n-1 may span at most 4096 pages (65 536 rows); more is HAT_EINVAL.
+ * All handles of one GPU share the array and it keeps the last call's page ids: calls that
+ * overlap on one GPU (different streams without ordering, or several handles at once) race on
+ * it -- order them on one stream, as consecutive calls on one handle already must be. */
+hat_status_t hat_mid_kv_export_static(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n,
+                                      void* k, void* v, void* hip_stream);
+
 /* Rows and GPU time of the last completed step -- the pair the cloud's state
  * monitor records every round (Sec. 3.2, Eq. 1-2).  Synchronises on the step's
  * end event. */

@@ -22,6 +22,7 @@ DUMP_IDS = {"xnorm": 0, "q": 1, "attn": 2, "xnorm2": 3, "act": 4}
 EXPORTED_SYMBOLS = [
     "hat_mid_kv_bytes", "hat_mid_workspace_bytes", "hat_mid_create", "hat_mid_forward", "hat_mid_forward_host", "hat_mid_release",
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_compact", "hat_mid_kv_import", "hat_mid_kv_export",
+    "hat_mid_kv_export_static",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
     "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_plan", "hat_mid_debug_create_host_only", "hat_mid_debug_plan",
     "hat_mid_debug_set_attn_targets", "hat_mid_debug_limit_plan",
@@ -95,6 +96,8 @@ def load_library():
     lib.hat_mid_kv_import.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
     lib.hat_mid_kv_export.restype = i32
     lib.hat_mid_kv_export.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
+    lib.hat_mid_kv_export_static.restype = i32
+    lib.hat_mid_kv_export_static.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
     lib.hat_mid_last_step_stats.restype = i32
     lib.hat_mid_last_step_stats.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_float)]
     lib.hat_mid_set_profiling.restype = i32
@@ -274,6 +277,14 @@ class HatMid:
         self._check(self.lib.hat_mid_kv_export(self._handle, device_id, layer, pos0, n, k.data_ptr(), v.data_ptr(),
                                                self._stream(stream)))
         return k, v
+
+    def kv_export_static(self, device_id, layer, pos0, n, k, v, stream=None):
+        """hat_mid_kv_export_static into the caller's k, v ([n, n_heads, head_dim] bf16 CUDA tensors): the
+        call itself allocates nothing and does not wait for the stream."""
+        assert k.is_cuda and k.dtype == self.torch.bfloat16 and k.is_contiguous() and k.shape == v.shape
+        assert tuple(k.shape) == (n, self.n_heads, self.head_dim) and v.is_contiguous()
+        self._check(self.lib.hat_mid_kv_export_static(self._handle, device_id, layer, pos0, n, k.data_ptr(),
+                                                      v.data_ptr(), self._stream(stream)))
 
     def last_step_stats(self):
         tok, ms = C.c_int32(), C.c_float()

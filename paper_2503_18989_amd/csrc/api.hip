@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <set>
 #include <string>
 #include <vector>
@@ -18,7 +19,34 @@
 #include "hat_kernels.h"
 #include "hat_layout.h"
 
+// ---- static scratch of hat_mid_kv_export_static -------------------------------------------------
+// Page ids of the rows being exported, staged here instead of in the caller's workspace.  One copy
+// of the array exists on every GPU the library is loaded on (16 KB each, held until the process
+// ends).  In host code the array's NAME is only a handle for hipGetSymbolAddress: the address a
+// kernel may use is the one that call returns, taken once per device with that device current.
+constexpr int kStaticPageIds = 4096;   // 4096 pages = 65 536 cache rows per call
+static __device__ __align__(256) int32_t scratch[kStaticPageIds];
+
 namespace {
+
+constexpr int kMaxGpus = 64;
+std::mutex g_scratch_mu;
+int32_t* g_scratch_ptr[kMaxGpus] = {};   // device address of `scratch` on each GPU (nullptr: not taken yet)
+
+// Address of the current device's copy of `scratch`, taken on first use on that device.
+hipError_t static_scratch(int device, int32_t** out) {
+  if (device < 0 || device >= kMaxGpus) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = (int32_t*)p;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
@@ -186,6 +214,14 @@ struct hat_mid {
   std::vector<PageOp> undo_pages;
   std::vector<std::pair<int32_t, DeviceState>> undo_dev;
   bool undo_on = false;
+
+  // hat_mid_kv_export_static: this GPU's copy of the static scratch array, a pinned host buffer for
+  // the page ids on their way there, and the event that says the last upload has read it
+  int device = -1;
+  int32_t* static_pages_dev = nullptr;
+  int32_t* static_pages_host = nullptr;
+  hipEvent_t static_ev = nullptr;
+  bool static_ev_used = false;
 
   hipStream_t last_stream = nullptr;       // stream of the most recent enqueue (hat_mid_destroy waits for it)
   bool used_stream = false;
@@ -364,6 +400,11 @@ static hat_status_t create_impl(const hat_mid_config_t* cfg, const hat_mid_layer
       return bail(e, "pinned plan buffer");
     if ((e = hipEventCreateWithFlags(&h->plan_ev[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
   }
+  if ((e = hipGetDevice(&h->device)) != hipSuccess) return bail(e, "current device");
+  if ((e = static_scratch(h->device, &h->static_pages_dev)) != hipSuccess) return bail(e, "address of the static scratch array");
+  if ((e = hipHostMalloc((void**)&h->static_pages_host, kStaticPageIds * sizeof(int32_t), hipHostMallocDefault)) != hipSuccess)
+    return bail(e, "pinned page-id buffer");
+  if ((e = hipEventCreateWithFlags(&h->static_ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
   if ((e = hipStreamCreateWithFlags(&h->copy_stream, hipStreamNonBlocking)) != hipSuccess) return bail(e, "copy stream");
   for (int i = 0; i < 2; ++i) {
     if ((e = hipEventCreateWithFlags(&h->up_done[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
@@ -424,6 +465,8 @@ void hat_mid_destroy(hat_mid_t* h) {
   }
   if (h->ev_begin) (void)hipEventDestroy(h->ev_begin);
   if (h->ev_end) (void)hipEventDestroy(h->ev_end);
+  if (h->static_ev) (void)hipEventDestroy(h->static_ev);
+  if (h->static_pages_host) (void)hipHostFree(h->static_pages_host);
   for (int i = 0; i < 2; ++i) {
     if (h->up_done[i]) (void)hipEventDestroy(h->up_done[i]);
     if (h->slot_free[i]) (void)hipEventDestroy(h->slot_free[i]);
@@ -1018,6 +1061,33 @@ hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, i
   hat_status_t rc = fixture_pages(h, d, pos0, n, st);
   if (rc != HAT_OK) return rc;
   HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages, pos0, n,
+                                  (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, st));
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_kv_export_static(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n, void* k,
+                                      void* v, void* hip_stream) {
+  if (!h) return HAT_EINVAL;
+  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle has no GPU side");
+  const hat_mid_config_t& c = h->cfg;
+  if (device_id < 0 || device_id >= c.max_devices) return fail(h, HAT_EDEVICE, "device id %d out of range", device_id);
+  if (layer < 0 || layer >= c.n_layers || n <= 0 || pos0 < 0 || !k || !v) return fail(h, HAT_EINVAL, "bad export arguments");
+  const DeviceState& d = h->dev[device_id];
+  if ((long)pos0 + n > d.len) return fail(h, HAT_EPOS, "export of rows %d..%ld beyond cache length %d", pos0, (long)pos0 + n, d.len);
+  const int p0 = pos0 >> 4, p1 = (pos0 + n - 1) >> 4, np = p1 - p0 + 1;
+  if (np > kStaticPageIds)
+    return fail(h, HAT_EINVAL, "export of %d rows spans %d pages: the static scratch holds %d page ids (%d rows)", n, np,
+                kStaticPageIds, kStaticPageIds * HAT_PAGE_SIZE);
+  hipStream_t st = (hipStream_t)hip_stream;
+  // the pinned buffer is free again once the previous call's upload has read it
+  if (h->static_ev_used) HIP_TRY(h, hipEventSynchronize(h->static_ev));
+  memcpy(h->static_pages_host, d.pages.data() + p0, (size_t)np * sizeof(int32_t));
+  note_stream(h, st);
+  // from here on only the address taken with hipGetSymbolAddress is used for the array
+  HIP_TRY(h, hipMemcpyAsync(h->static_pages_dev, h->static_pages_host, (size_t)np * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  HIP_TRY(h, hipEventRecord(h->static_ev, st));
+  h->static_ev_used = true;
+  HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->static_pages_dev, pos0, n,
                                   (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, st));
   return HAT_OK;
 }

@@ -1,0 +1,104 @@
+"""hat_mid_kv_export_static -- the export entry point for callers that may not allocate (its page ids
+are staged in an array that the library holds statically on the GPU) -- against hat_mid_kv_export,
+the entry point it is a variant of.  Integer / byte work: the exported rows must be bit-identical.
+Two calls in a row on one stream with no synchronisation between them, the second with a smaller
+input (the array then still holds page ids of the first call beyond those the second one wrote),
+then a second handle on the same GPU (it shares the array), and the size limit."""
+import numpy as np
+import pytest
+
+import hat_inputs as hi
+from gpu_util import dev_weights, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+CFG = dict(name="small128", n_layers=2, d_model=512, n_heads=4, head_dim=128, d_ffn=1408, rms_eps=1e-5, rope_theta=1e4)
+
+
+def make(seed, n_pages, max_pos):
+    from paper_2503_18989_amd import HatMid
+    ws = [hi.layer_weights(CFG, l, seed) for l in range(CFG["n_layers"])]
+    return HatMid(CFG, [dev_weights(w) for w in ws], n_pages=n_pages, max_devices=4, max_step_tokens=256, max_pos=max_pos)
+
+
+def fill(m, dev, n, seed):
+    """n cache rows of every layer by import, in interleaved page order with another device so that the
+    page list is not a plain run of consecutive ids."""
+    H, hd = CFG["n_heads"], CFG["head_dim"]
+    for l in range(CFG["n_layers"]):
+        k, v = hi.kv_prefix(n, H, hd, seed, dev, l)
+        for q in range(0, n, 48):
+            e = min(q + 48, n)
+            m.kv_import(dev, l, q, to_dev_bf16(k[q:e]).view(-1, H, hd), to_dev_bf16(v[q:e]).view(-1, H, hd))
+            if l == 0:     # another device takes the pages in between
+                m.kv_import(3, 0, (q // 48) * 16, to_dev_bf16(k[:16]).view(-1, H, hd), to_dev_bf16(v[:16]).view(-1, H, hd))
+
+
+def test_static_export_equals_export_on_two_calls_in_a_row():
+    import torch
+    H, hd = CFG["n_heads"], CFG["head_dim"]
+    m = make(7, n_pages=200, max_pos=2048)
+    fill(m, 0, 1000, 7)
+    fill(m, 1, 333, 8)
+    assert m.kv_query(0)[1] != list(range(len(m.kv_query(0)[1]))), "the page list was meant to be scattered"
+    # outputs are the caller's, made before the calls: the entry point itself allocates nothing
+    cases = [(0, 1, 5, 990), (1, 0, 100, 37)]          # (device, layer, pos0, n): the second is smaller
+    outs = [(torch.full((n, H, hd), 7.0, dtype=torch.bfloat16, device="cuda"),
+             torch.full((n, H, hd), 7.0, dtype=torch.bfloat16, device="cuda")) for _, _, _, n in cases]
+    torch.cuda.synchronize()
+    for (dev, l, p0, n), (k, v) in zip(cases, outs):
+        m.kv_export_static(dev, l, p0, n, k, v)        # back to back, no synchronisation in between
+    torch.cuda.synchronize()
+    for (dev, l, p0, n), (k, v) in zip(cases, outs):
+        kr, vr = m.kv_export(dev, l, p0, n)
+        torch.cuda.synchronize()
+        assert torch.equal(k.view(torch.int16), kr.view(torch.int16)), (dev, l, p0, n)
+        assert torch.equal(v.view(torch.int16), vr.view(torch.int16)), (dev, l, p0, n)
+        # and both equal the values that were imported
+        kk, vv = hi.kv_prefix(1000 if dev == 0 else 333, H, hd, 7 if dev == 0 else 8, dev, l)
+        assert np.array_equal(k.float().cpu().numpy(), kk[p0:p0 + n]) and np.array_equal(v.float().cpu().numpy(), vv[p0:p0 + n])
+    # a second handle on the same GPU uses the same array: a call on it, then the first handle again
+    m2 = make(9, n_pages=64, max_pos=512)
+    fill(m2, 2, 200, 9)
+    k2 = torch.empty((150, H, hd), dtype=torch.bfloat16, device="cuda"); v2 = torch.empty_like(k2)
+    m2.kv_export_static(2, 1, 50, 150, k2, v2)
+    k1 = torch.empty((16, H, hd), dtype=torch.bfloat16, device="cuda"); v1 = torch.empty_like(k1)
+    m.kv_export_static(0, 0, 984, 16, k1, v1)
+    torch.cuda.synchronize()
+    kr, vr = m2.kv_export(2, 1, 50, 150)
+    assert torch.equal(k2.view(torch.int16), kr.view(torch.int16)) and torch.equal(v2.view(torch.int16), vr.view(torch.int16))
+    kr, vr = m.kv_export(0, 0, 984, 16)
+    assert torch.equal(k1.view(torch.int16), kr.view(torch.int16)) and torch.equal(v1.view(torch.int16), vr.view(torch.int16))
+    m2.close(); m.close()
+
+
+def test_static_export_rejects_what_does_not_fit_and_what_export_rejects():
+    import torch
+    from paper_2503_18989_amd import HatError
+    H, hd = CFG["n_heads"], CFG["head_dim"]
+    limit_rows = 4096 * 16
+    m = make(11, n_pages=4096 + 8, max_pos=limit_rows + 64)
+    # one layer's cache of limit + 32 rows (values do not matter: one block imported over and over)
+    blk_k, blk_v = hi.kv_prefix(2048, H, hd, 11, 0, 0)
+    dk, dv = to_dev_bf16(blk_k).view(-1, H, hd), to_dev_bf16(blk_v).view(-1, H, hd)
+    for q in range(0, limit_rows, 2048):
+        m.kv_import(0, 0, q, dk, dv)
+    m.kv_import(0, 0, limit_rows, dk[:32], dv[:32])
+    k = torch.empty((limit_rows + 64, H, hd), dtype=torch.bfloat16, device="cuda"); v = torch.empty_like(k)
+    with pytest.raises(HatError) as e:
+        m.kv_export_static(0, 0, 0, limit_rows + 32, k[:limit_rows + 32], v[:limit_rows + 32])   # 4098 pages
+    assert e.value.code == -1 and "static scratch" in str(e.value)
+    with pytest.raises(HatError) as e:
+        m.kv_export_static(0, 0, 15, limit_rows - 14 + 1, k[:limit_rows - 13], v[:limit_rows - 13])   # rows 15 .. 65537: 4097 pages
+    assert e.value.code == -1
+    # exactly the limit passes and is exact: 4096 pages starting inside a page
+    m.kv_export_static(0, 0, 16, limit_rows, k[:limit_rows], v[:limit_rows])
+    torch.cuda.synchronize()
+    kr, vr = m.kv_export(0, 0, 16, limit_rows)
+    assert torch.equal(k[:limit_rows].view(torch.int16), kr.view(torch.int16)) and torch.equal(v[:limit_rows].view(torch.int16), vr.view(torch.int16))
+    for args, code in (((0, 0, 0, limit_rows + 64), -3), ((9, 0, 0, 4), -5), ((0, 5, 0, 4), -1), ((1, 0, 0, 4), -3)):
+        n = args[3]
+        with pytest.raises(HatError) as e:
+            m.kv_export_static(*args, k[:n], v[:n])
+        assert e.value.code == code, (args, e.value)
+    m.close()
