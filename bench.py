@@ -18,6 +18,8 @@ Besides the contract line it reports, in the same JSON object:
                 per step and with one device per step: GPU time per step against chunk size and prefix
                 (the cost profile g(.)), chunk-attention MFMA / min-roofline fraction per chunk size,
                 and the chunk sizes the library's scheduler (Eq. 3) derives for a few uplinks
+  measured_peaks  microbenchmarks built into the library (streaming read / copy, matrix-core loop, direct-to-LDS
+                load path): the measured ceilings next to the published peaks
   cpu_baseline  the CPU oracle timed on this host on a bounded sample
   host_fed      the same workload with hidden states in pinned host memory (PCIe-inclusive; not the metric)
   paper_context end-to-end numbers the paper reports on other hardware
@@ -236,6 +238,14 @@ def attention_legs(cfg7, dev_layers):
                               traffic_source="profiles/traffic_attention_legs.txt (recorded rocprofv3 --pmc runs, not measured in this run)",
                               workload="30 devices x 5 rows, cache lengths U[1024,8192], 7B-shaped layer")
     out["verify_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
+    # the same launch with the kernel's arithmetic taken out (hat_mid_debug_set_verify_probe): what this
+    # access order -- head-major pool, page-list walk, one register stage per wave -- can reach here
+    m.set_verify_probe(True)
+    sec_p = profile_classes(m, lambda: [vstep() for _ in range(8)])["attn_verify"][0]
+    m.set_verify_probe(False)
+    out["verify_attn"]["loads_only"] = {"us_per_launch": sec_p * 1e6, "GBps": by / sec_p / 1e9, "frac_of_peak": by / sec_p / PEAK_HBM,
+                                        "kernel_vs_loads_only": sec_p / sec}
+    vstep()     # a real step again: the probe leaves the verify rows' attention output unwritten
     ms = timed_steps(vstep, 8)
     out["verify_step"] = {"tokens": 150, "layers": n_layers, "gpu_ms": ms, "hidden_tokens_per_s": 150 / (ms * 1e-3),
                           "roofline": out["verify_attn"]}
@@ -390,6 +400,28 @@ def chunk_size_rule(points, d):
     return out
 
 
+# ---------------------------------------------------------------- measured peaks (microbenchmarks in the library)
+def measured_peaks():
+    """hat_mid_debug_peak: what the chip delivers through the instruction mixes of this library's kernels."""
+    from paper_2503_18989_amd.binding import measure_peak
+    out = {}
+    for kind, unit, peak in (("stream_read", "GB/s", PEAK_HBM), ("stream_read_nt", "GB/s", PEAK_HBM), ("copy", "GB/s", PEAK_HBM),
+                             ("mfma_f16", "TFLOP/s", PEAK_MFMA_BF16), ("lds_load", "GB/s", None)):
+        r = measure_peak(kind, nbytes=(1 << 30) if kind != "copy" else (2 << 30), iters=20)
+        e = {"value": r / (1e12 if unit == "TFLOP/s" else 1e9), "unit": unit}
+        if peak:
+            e["frac_of_published_peak"] = r / peak
+        if kind == "mfma_f16":
+            e["implied_clock_GHz"] = r / (256 * 4 * 1024.0) / 1e9    # 4 SIMDs x 1024 FLOP per clock per CU
+        if kind == "lds_load":
+            e["bytes_per_clock_per_cu_at_2.4GHz"] = r / 256 / 2.4e9
+        out[kind] = e
+    out["note"] = ("stream_read*: 1 GiB read once per launch, every wave a contiguous span in 16 KB steps (16 loads of 16 bytes per "
+                   "lane in flight, 32 waves per CU); copy: 1 GiB read + 1 GiB written; mfma_f16: 32x32x16 fp16 matrix instructions only, two waves per SIMD; lds_load: direct-to-LDS "
+                   "loads of a cache-resident 1 MiB region, one 4-wave workgroup per CU, 16 loads in flight per wave")
+    return out
+
+
 # ---------------------------------------------------------------- measured HBM traffic (from profiles/)
 def recorded_traffic(kernel):
     """HBM bytes per launch of a kernel class as measured by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
@@ -448,6 +480,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override depth (for profiling runs; the line is then not the metric)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the 13B-shaped chunk-size sweep")
     ap.add_argument("--sweep-layers", type=int, default=38, help="depth of the chunk-size sweep model")
+    ap.add_argument("--peaks", action="store_true", help="only the machine microbenchmarks (hat_mid_debug_peak): prints them as JSON and exits")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling FETCH_SIZE/WRITE_SIZE counters)")
     a = ap.parse_args()
@@ -458,6 +491,9 @@ def main():
 
     import torch
     from paper_2503_18989_amd import HatMid
+    if a.peaks:
+        print(json.dumps({"measured_peaks": measured_peaks()}))
+        return
     cfg = dict(hi.MID7B)
     if a.layers:
         cfg = hi.with_layers(cfg, a.layers)
@@ -512,6 +548,7 @@ def main():
     del m
     torch.cuda.empty_cache()
 
+    peaks = measured_peaks()
     legs = None
     if not a.no_legs:
         legs = attention_legs(cfg, dev_layers)
@@ -542,7 +579,7 @@ def main():
                    "mfma_operands": "fp16 (fp32 accumulate)"},
         "gpu_event_ms_per_step": gpu_s / a.steps * 1e3, "host_wall_ms_per_step": wall / a.steps * 1e3,
         "step_roofline_ms": ideal * 1e3, "step_roofline_frac": ideal / (sec / a.steps),
-        "roofline": roofline, "kernels": kernels, "legs": legs, "chunk_size_sweep": sweep, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "measured_peaks": peaks, "legs": legs, "chunk_size_sweep": sweep, "cpu_baseline": cpu,
         "host_fed": host_fed,
         "paper_context": "paper reports end-to-end TTFT -41..54% / TBT -41..77% on 30 Jetson devices + 8xA6000 "
                          "(other hardware, whole system): context only, not a target",

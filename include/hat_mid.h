@@ -331,6 +331,30 @@ hat_status_t hat_mid_debug_set_attn_targets(hat_mid_t* h, int32_t chunk_target, 
  * movements, and check that they are undone. */
 hat_status_t hat_mid_debug_limit_plan(hat_mid_t* h, int64_t max_words);
 
+/* on != 0: later forwards run, in place of verify attention, a kernel that performs exactly its
+ * memory accesses (same work items, page-list walk, load instructions and order) and none of its
+ * arithmetic.  The step's OUTPUTS ARE THEN MEANINGLESS (the attention output of verify rows is
+ * left as it was); the cache is still appended to.  hat_mid_kernel_times reports the probe under
+ * HAT_K_ATTN_VERIFY: its duration is the ceiling this access order can reach on the machine. */
+hat_status_t hat_mid_debug_set_verify_probe(hat_mid_t* h, int32_t on);
+
+/* Microbenchmarks of the machine (no handle needed): the rates that the instruction mixes used
+ * by this library's kernels reach on their own, for reading roofline fractions against measured
+ * as well as published peaks.  buf: device scratch of `bytes` (16-byte aligned; at least 1 MiB,
+ * for the streaming kinds as large as the stream to be measured, e.g. 1 GiB); iters launches
+ * (1..1000) are timed with HIP events on hip_stream after one warm-up launch, and the call waits
+ * for them.  *rate: bytes/s (STREAM_READ*, COPY: read + written bytes; LDS_LOAD: bytes moved into
+ * LDS by direct-to-LDS loads from a 1 MiB cache-resident region, all CUs together) or FLOP/s
+ * (MFMA_F16: 32x32x16 fp16 matrix instructions only, two waves per SIMD). */
+typedef enum {
+  HAT_PEAK_STREAM_READ = 0,
+  HAT_PEAK_STREAM_READ_NT = 1,   /* the same with non-temporal loads */
+  HAT_PEAK_COPY = 2,
+  HAT_PEAK_MFMA_F16 = 3,
+  HAT_PEAK_LDS_LOAD = 4
+} hat_peak_kind_t;
+hat_status_t hat_mid_debug_peak(int32_t kind, void* buf, size_t bytes, int32_t iters, void* hip_stream, double* rate);
+
 /* Number of entries in the library's GEMM tile table (valid `tile` values of
  * hat_mid_debug_force_gemm are 0 .. count-1).  No GPU work. */
 int32_t hat_mid_debug_gemm_tile_count(void);

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "hat_mid_kv_export_static",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
     "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_plan", "hat_mid_debug_create_host_only", "hat_mid_debug_plan",
-    "hat_mid_debug_set_attn_targets", "hat_mid_debug_limit_plan",
+    "hat_mid_debug_set_attn_targets", "hat_mid_debug_limit_plan", "hat_mid_debug_set_verify_probe", "hat_mid_debug_peak",
     "hat_sched_create", "hat_sched_destroy", "hat_sched_observe", "hat_sched_mu", "hat_sched_predict",
     "hat_sched_chunk_size", "hat_sched_parallel_draft_steps",
 ]
@@ -116,6 +116,10 @@ def load_library():
     lib.hat_mid_debug_create_host_only.argtypes = [C.POINTER(Config), C.POINTER(vp)]
     lib.hat_mid_debug_set_attn_targets.restype = i32
     lib.hat_mid_debug_set_attn_targets.argtypes = [vp, i32, i32]
+    lib.hat_mid_debug_set_verify_probe.restype = i32
+    lib.hat_mid_debug_set_verify_probe.argtypes = [vp, i32]
+    lib.hat_mid_debug_peak.restype = i32
+    lib.hat_mid_debug_peak.argtypes = [i32, vp, C.c_size_t, i32, vp, C.POINTER(C.c_double)]
     lib.hat_mid_debug_limit_plan.restype = i32
     lib.hat_mid_debug_limit_plan.argtypes = [vp, C.c_int64]
     pi = C.POINTER(i32)
@@ -316,6 +320,10 @@ class HatMid:
     def set_attn_targets(self, chunk_target=0, verify_target=0):
         self._check(self.lib.hat_mid_debug_set_attn_targets(self._handle, chunk_target, verify_target))
 
+    def set_verify_probe(self, on):
+        """Measurement aid: verify attention replaced by its loads only -- outputs become meaningless."""
+        self._check(self.lib.hat_mid_debug_set_verify_probe(self._handle, 1 if on else 0))
+
     def close(self):
         if getattr(self, "_handle", None) is not None and self._handle.value:
             self.lib.hat_mid_destroy(self._handle)
@@ -326,6 +334,23 @@ class HatMid:
             self.close()
         except Exception:
             pass
+
+
+PEAK_KINDS = {"stream_read": 0, "stream_read_nt": 1, "copy": 2, "mfma_f16": 3, "lds_load": 4}
+
+
+def measure_peak(kind, nbytes=1 << 30, iters=20):
+    """hat_mid_debug_peak on a scratch tensor of nbytes: bytes/s or FLOP/s (see include/hat_mid.h)."""
+    import torch
+    lib = load_library()
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    buf.zero_()
+    rate = C.c_double()
+    rc = lib.hat_mid_debug_peak(PEAK_KINDS[kind], buf.data_ptr(), nbytes, iters,
+                                C.c_void_p(torch.cuda.current_stream().cuda_stream), C.byref(rate))
+    if rc != 0:
+        raise HatError(rc, "hat_mid_debug_peak(%s) failed" % kind)
+    return rate.value
 
 
 class HatPlanner:

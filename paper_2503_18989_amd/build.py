@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhatmid.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "sched.cpp"]   # sched.cpp: host code only
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "peaks.hip", "sched.cpp"]   # sched.cpp: host code only
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
          "-Wno-unused-result"]
@@ -29,7 +29,7 @@ def _compile(src):
 
 
 def build(verbose=True):
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)

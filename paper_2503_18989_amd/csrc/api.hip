@@ -226,6 +226,7 @@ struct hat_mid {
   hipStream_t last_stream = nullptr;       // stream of the most recent enqueue (hat_mid_destroy waits for it)
   bool used_stream = false;
   size_t plan_limit = 0;                   // > 0: lowered plan capacity (hat_mid_debug_limit_plan)
+  bool verify_probe = false;               // verify attention replaced by its loads-only twin (hat_mid_debug_set_verify_probe)
 
   bool host_only = false;                  // built by hat_mid_debug_create_host_only: no GPU memory, no HIP calls
   std::vector<int32_t> host_plan;          // its plan words
@@ -839,7 +840,10 @@ static hat_status_t enqueue_step(hat_mid_t* h, const StepPlan& sp, const int32_t
     }
     if (sp.n_vitems > 0) {
       a.items = (const HatAttnItem*)(D + o_vi); a.n_items = sp.n_vitems;
-      LAUNCH(h, st, HAT_K_ATTN_VERIFY, hat_launch_attn_verify(pd, a, st));
+      if (h->verify_probe)
+        LAUNCH(h, st, HAT_K_ATTN_VERIFY, hat_launch_attn_verify_probe(pd, a, (uint32_t*)h->b.fixture_pages, st));
+      else
+        LAUNCH(h, st, HAT_K_ATTN_VERIFY, hat_launch_attn_verify(pd, a, st));
     }
     if (sp.n_mitems > 0)
       LAUNCH(h, st, HAT_K_ATTN_MERGE, hat_launch_attn_merge(a, (const HatMergeItem*)(D + o_mi), sp.n_mitems, st));
@@ -1159,6 +1163,13 @@ hat_status_t hat_mid_debug_set_attn_targets(hat_mid_t* h, int32_t chunk_target, 
   if (!h || chunk_target < 0 || verify_target < 0) return HAT_EINVAL;
   if (chunk_target > 0) h->s.attn_target = chunk_target;
   if (verify_target > 0) h->s.verify_target = verify_target;
+  return HAT_OK;
+}
+
+hat_status_t hat_mid_debug_set_verify_probe(hat_mid_t* h, int32_t on) {
+  if (!h) return HAT_EINVAL;
+  if (h->host_only) return fail(h, HAT_EINVAL, "a host-only handle has no GPU side");
+  h->verify_probe = on != 0;
   return HAT_OK;
 }
 

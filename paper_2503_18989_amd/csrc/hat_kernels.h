@@ -132,6 +132,8 @@ struct HatAttn {
 hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStream_t st);
 hipError_t hat_launch_attn_verify(const HatPlanDev& p, const HatAttn& a, hipStream_t st);
 hipError_t hat_launch_attn_merge(const HatAttn& a, const HatMergeItem* items, int n_items, hipStream_t st);
+// the verify kernel's loads without its arithmetic (a measurement aid; writes nothing but *sink, and that never)
+hipError_t hat_launch_attn_verify_probe(const HatPlanDev& p, const HatAttn& a, uint32_t* sink, hipStream_t st);
 
 // ---- fixtures ------------------------------------------------------------------
 // k, v: [n, H, hd] bf16 plain; pages: device array of the page ids covering the rows

@@ -24,7 +24,7 @@ hipError_t hat_launch_rope_append(const HatPlanDev&, act_t*, const float2*, bf16
 hipError_t hat_launch_attn_chunk(const HatPlanDev&, const HatAttn&, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_attn_verify(const HatPlanDev&, const HatAttn&, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_attn_merge(const HatAttn&, const HatMergeItem*, int, hipStream_t) { return hipErrorUnknown; }
-hipError_t hat_attn_init() { return hipErrorUnknown; }
+hipError_t hat_launch_attn_verify_probe(const HatPlanDev&, const HatAttn&, uint32_t*, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_kv_import(bf16_t*, int, const int32_t*, int, int, const bf16_t*, const bf16_t*, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_kv_move(bf16_t*, size_t, int, int, const HatRowMoves&, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_kv_export(const bf16_t*, int, const int32_t*, int, int, bf16_t*, bf16_t*, int, int, hipStream_t) { return hipErrorUnknown; }
