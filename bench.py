@@ -172,6 +172,68 @@ def run_cfg2_host(m, cfg, steps, warmup, n_chunks=8, chunk=256):
             "note": "hidden states start and end in pinned host memory (hat_mid_forward_host); never the headline value"}
 
 
+def uplink_emulation(m, cfg, step_ms, n_chunks=8, chunk=256):
+    """Time to the last deep hidden state of a 2048-row prompt (the cloud's share of the time to first token)
+    when the device's hidden states arrive over an uplink of beta_up bytes/s (Sec. 3.3): with the paper's prompt
+    chunking -- a chunk is uploaded (PCIe) and processed as soon as it has arrived, while the next one is still
+    on the air -- against the plain U-shaped order, where the whole prompt has to arrive first.  The uplink is
+    emulated on the host: chunk j is handed to hat_mid_forward_host at (j + 1) * chunk * A / beta_up after the
+    start, A = 2 d bytes per row; everything from there on (H2D on the library's copy stream, the step, D2H) is
+    real.  Rates: the paper's WiFi (10 MB/s), 100 MB/s, the rate at which a chunk takes as long to arrive as to
+    process (where Eq. 3 puts the chunk size), and 1 GB/s."""
+    import torch
+    from paper_2503_18989_amd.binding import CSegment
+    stream = torch.cuda.current_stream()
+    sp = C.c_void_p(stream.cuda_stream)
+    A = 2 * cfg["d_model"]
+    xs, outs, arrs = [], [], []
+    for i in range(n_chunks):
+        x = torch.from_numpy(hi.bf16_bits(hi.hidden_rows(chunk, cfg["d_model"], SEED, i)).view(np.int16)).view(torch.bfloat16).pin_memory()
+        o = torch.empty_like(x).pin_memory()
+        arr = (CSegment * 1)()
+        arr[0] = CSegment(0, hi.CHUNK, chunk, i * chunk, x.data_ptr(), o.data_ptr())
+        xs.append(x); outs.append(o); arrs.append(arr)
+
+    def run(beta, overlap):
+        m.release(0)
+        torch.cuda.synchronize()
+        per_chunk = chunk * A / beta
+        t0 = time.perf_counter()
+
+        def wait_until(t):
+            while True:
+                dt = t0 + t - time.perf_counter()
+                if dt <= 0:
+                    return
+                time.sleep(dt if dt > 2e-3 else 0)      # sleep, then spin over the last 2 ms
+        if overlap:
+            for j in range(n_chunks):
+                wait_until((j + 1) * per_chunk)
+                rc = m.lib.hat_mid_forward_host(m._handle, arrs[j], 1, sp)
+                if rc != 0:
+                    m._check(rc)
+        else:
+            wait_until(n_chunks * per_chunk)
+            for j in range(n_chunks):
+                rc = m.lib.hat_mid_forward_host(m._handle, arrs[j], 1, sp)
+                if rc != 0:
+                    m._check(rc)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    balanced = chunk * A / (step_ms * 1e-3)
+    rows = []
+    for name, beta in (("10 MB/s (the paper's WiFi)", 10e6), ("100 MB/s", 100e6), ("balanced: chunk arrives in one step time", balanced),
+                       ("1 GB/s", 1e9)):
+        run(beta if beta > 50e6 else 1e9, True)      # warm
+        a = min(run(beta, True) for _ in range(2))
+        b = min(run(beta, False) for _ in range(2))
+        rows.append({"uplink": name, "beta_up_MB_per_s": beta / 1e6, "upload_ms_whole_prompt": n_chunks * chunk * A / beta * 1e3,
+                     "ms_with_overlap": a, "ms_without_overlap": b, "saved_ms": b - a})
+    return {"workload": "2048-row prompt as %d chunks of %d, 7B-shaped, %d layers; A = %d bytes per row" % (n_chunks, chunk, cfg["n_layers"], A),
+            "what": "time from the start of the upload to the last chunk's deep hidden states back in host memory", "by_uplink": rows}
+
+
 def profile_classes(m, run_steps):
     """Per kernel class: (avg seconds per launch, launches) with event bracketing on."""
     import torch
@@ -480,6 +542,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override depth (for profiling runs; the line is then not the metric)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the 13B-shaped chunk-size sweep")
     ap.add_argument("--sweep-layers", type=int, default=38, help="depth of the chunk-size sweep model")
+    ap.add_argument("--host-fed-only", action="store_true", help="only the headline workload, device-fed and host-fed, and the uplink emulation")
     ap.add_argument("--peaks", action="store_true", help="only the machine microbenchmarks (hat_mid_debug_peak): prints them as JSON and exits")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling FETCH_SIZE/WRITE_SIZE counters)")
@@ -511,6 +574,12 @@ def main():
     log("cfg2: %.3f ms/step, %.0f hidden tokens/s" % (sec / a.steps * 1e3, value))
     host_fed = run_cfg2_host(m, cfg, a.steps, a.warmup)
     log("cfg2 from host memory: %.3f ms/step, %.0f hidden tokens/s" % (host_fed["ms_per_step"], host_fed["value"]))
+    host_fed["uplink_emulation"] = uplink_emulation(m, cfg, sec / a.steps * 1e3)
+    for r in host_fed["uplink_emulation"]["by_uplink"]:
+        log("uplink %s: %.1f ms with overlap, %.1f ms without" % (r["uplink"], r["ms_with_overlap"], r["ms_without_overlap"]))
+    if a.host_fed_only:
+        print(json.dumps({"value": value, "ms_per_step": sec / a.steps * 1e3, "host_fed": host_fed}))
+        return
 
     # per-class timing (separate pass, events around every launch)
     def cyc():
