@@ -18,10 +18,10 @@
  * sub-block.  A row at absolute position p attends to keys 0..p of its own
  * device only.
  *
- * Arithmetic: weights and the KV cache hold bf16 values; matrix products take
- * fp16 operands (activations are produced in fp16, saturating; bf16 weights and
- * cache rows are widened to fp16, exact for magnitudes in [2^-17, 65504]) and
- * accumulate in fp32; softmax, normalisation, rotary embedding, SiLU and the
+ * Arithmetic: weights hold bf16 values, the KV cache bf16 or fp16 values
+ * (hat_kv_dtype_t); matrix products take fp16 operands (activations are produced
+ * in fp16, saturating; bf16 weights and bf16 cache rows are widened to fp16, exact
+ * for magnitudes in [2^-17, 65504]) and accumulate in fp32; softmax, normalisation, rotary embedding, SiLU and the
  * residual stream are fp32.  Supported activation range: every intermediate that
  * feeds a matrix product (norm outputs, q/k/v, attention outputs, the SwiGLU
  * product) is converted to fp16 with saturation, so a magnitude above 65504 is
@@ -81,6 +81,14 @@ typedef enum {
 
 typedef enum { HAT_SEG_CHUNK = 0, HAT_SEG_VERIFY = 1 } hat_seg_kind_t;
 typedef enum { HAT_BF16 = 0, HAT_F32 = 1 } hat_dtype_t;
+/* Element type of the KV cache (two bytes either way).  HAT_KV_BF16 is the format the workload
+ * definitions name.  HAT_KV_F16 keeps 11 instead of 8 significand bits: the rounding of cache rows is
+ * the largest error of the whole path (it is amplified from layer to layer), and a 38-layer stack of
+ * 13B-shaped random-init layers exceeds the 2e-2 parity bar with a bf16 cache (2.2e-2 measured) while
+ * an fp16 cache stays near 4e-3; fp16 elements are also matrix-core operands as they are, so the
+ * attention kernels skip the widening.  Cache values (keys, values of unit-scale activations) are far
+ * inside the fp16 range; anything beyond +-65504 saturates. */
+typedef enum { HAT_KV_BF16 = 0, HAT_KV_F16 = 1 } hat_kv_dtype_t;
 
 #define HAT_PAGE_SIZE 16  /* tokens per KV page */
 #define HAT_MAX_VERIFY 8  /* longest verify segment */
@@ -99,6 +107,7 @@ typedef struct {
   int32_t max_step_tokens; /* upper bound on the rows of one step */
   int32_t max_pos;         /* upper bound on any device's cache length */
   int32_t io_dtype;        /* hat_dtype_t of hidden_in / hidden_out */
+  int32_t kv_dtype;        /* hat_kv_dtype_t of the cache elements */
 } hat_mid_config_t;
 
 /* One layer's weights: device pointers to bf16 arrays, linear weights row-major
@@ -204,7 +213,8 @@ hat_status_t hat_mid_kv_query(const hat_mid_t* h, int32_t device_id, int32_t* kv
                               int32_t cap, int32_t* n_pages_out);
 
 /* Installs n cache rows of one layer at positions pos0..pos0+n-1 from device
- * arrays k, v of shape [n, n_heads, head_dim] bf16 (k already rotated).  Rows
+ * arrays k, v of shape [n, n_heads, head_dim] bf16 (k already rotated); an fp16
+ * cache holds those bf16 values exactly (magnitudes in [2^-17, 65504]).  Rows
  * must extend or overwrite the device's cache contiguously (pos0 <= length); the
  * length becomes max(length, pos0+n) and missing pages are taken with the same
  * lowest-free-id policy as forward.  Every layer has to be imported over the same
@@ -213,7 +223,8 @@ hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, i
                                const void* k, const void* v, void* hip_stream);
 
 /* Mirror of import: copies rows pos0..pos0+n-1 of one layer out to k, v
- * ([n, n_heads, head_dim] bf16 device arrays). */
+ * ([n, n_heads, head_dim] bf16 device arrays); rows of an fp16 cache are rounded
+ * to bf16 (to nearest even) on the way out, so imported rows come back unchanged. */
 hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, int32_t pos0, int32_t n,
                                void* k, void* v, void* hip_stream);
 

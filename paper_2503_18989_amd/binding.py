@@ -14,6 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 CHUNK, VERIFY = 0, 1
 HAT_BF16, HAT_F32 = 0, 1
+KV_DTYPES = {"bf16": 0, "f16": 1}
 STATUS = {0: "HAT_OK", -1: "HAT_EINVAL", -2: "HAT_ENOMEM", -3: "HAT_EPOS", -4: "HAT_EDUP", -5: "HAT_EDEVICE",
           -6: "HAT_EHIP"}
 KERNEL_NAMES = ["gather", "rmsnorm", "gemm_qkv", "rope_append", "attn_chunk", "attn_verify", "attn_merge",
@@ -35,7 +36,7 @@ class Config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("d_ffn", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("page_size", C.c_int32),
                 ("n_pages", C.c_int32), ("max_devices", C.c_int32), ("max_step_tokens", C.c_int32),
-                ("max_pos", C.c_int32), ("io_dtype", C.c_int32)]
+                ("max_pos", C.c_int32), ("io_dtype", C.c_int32), ("kv_dtype", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -163,7 +164,7 @@ class HatMid:
     """
 
     def __init__(self, cfg, layers, n_pages, max_devices=64, max_step_tokens=8192, max_pos=16384,
-                 io_dtype="bf16", stream=None):
+                 io_dtype="bf16", kv_dtype="bf16", stream=None):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -172,7 +173,8 @@ class HatMid:
         self.io_torch = torch.bfloat16 if io_dtype == "bf16" else torch.float32
         self.cfg = Config(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"],
                           cfg["rms_eps"], cfg["rope_theta"], 16, n_pages, max_devices, max_step_tokens, max_pos,
-                          HAT_BF16 if io_dtype == "bf16" else HAT_F32)
+                          HAT_BF16 if io_dtype == "bf16" else HAT_F32, KV_DTYPES[kv_dtype])
+        self.kv_dtype = kv_dtype
         self.d = cfg["d_model"]
         self.d_ffn = cfg["d_ffn"]
         self.n_heads, self.head_dim = cfg["n_heads"], cfg["head_dim"]
@@ -364,7 +366,7 @@ class HatPlanner:
         self.lib = load_library()
         self.max_step_tokens = max_step_tokens
         self.ccfg = Config(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"],
-                           cfg["rms_eps"], cfg["rope_theta"], 16, n_pages, max_devices, max_step_tokens, max_pos, HAT_BF16)
+                           cfg["rms_eps"], cfg["rope_theta"], 16, n_pages, max_devices, max_step_tokens, max_pos, HAT_BF16, 0)
         self._handle = C.c_void_p()
         rc = self.lib.hat_mid_debug_create_host_only(C.byref(self.ccfg), C.byref(self._handle))
         if rc != 0:

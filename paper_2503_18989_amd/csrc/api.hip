@@ -78,6 +78,7 @@ bool valid_cfg(const hat_mid_config_t* c) {
   if (c->page_size != HAT_PAGE_SIZE || c->n_pages <= 0) return false;
   if (c->max_devices <= 0 || c->max_step_tokens <= 0 || c->max_pos <= 0) return false;
   if (c->io_dtype != HAT_BF16 && c->io_dtype != HAT_F32) return false;
+  if (c->kv_dtype != HAT_KV_BF16 && c->kv_dtype != HAT_KV_F16) return false;
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return false;
   return true;
 }
@@ -182,7 +183,7 @@ struct hat_mid {
   hat_mid_config_t cfg;
   Shapes s;
   Buffers b;
-  bf16_t* pool;
+  kv_t* pool;
   size_t layer_pool_elems;
 
   std::set<int32_t> free_pages;
@@ -359,7 +360,7 @@ extern "C" {
 
 size_t hat_mid_kv_bytes(const hat_mid_config_t* cfg) {
   if (!valid_cfg(cfg)) return 0;
-  return (size_t)cfg->n_layers * cfg->n_pages * kv_page_elems(cfg->n_heads, cfg->head_dim) * sizeof(bf16_t);
+  return (size_t)cfg->n_layers * cfg->n_pages * kv_page_elems(cfg->n_heads, cfg->head_dim) * sizeof(kv_t);
 }
 
 size_t hat_mid_workspace_bytes(const hat_mid_config_t* cfg) {
@@ -383,7 +384,7 @@ static hat_status_t create_impl(const hat_mid_config_t* cfg, const hat_mid_layer
   h->cfg = *cfg;
   h->s = make_shapes(*cfg);
   carve(*cfg, h->s, workspace, &h->b);
-  h->pool = (bf16_t*)kv_pool;
+  h->pool = (kv_t*)kv_pool;
   h->layer_pool_elems = (size_t)cfg->n_pages * kv_page_elems(cfg->n_heads, cfg->head_dim);
   for (int i = 0; i < cfg->n_pages; ++i) h->free_pages.insert(i);
   h->dev.resize(cfg->max_devices);
@@ -821,7 +822,7 @@ static hat_status_t enqueue_step(hat_mid_t* h, const StepPlan& sp, const int32_t
   };
   for (int l = 0; l < s.L; ++l) {
     const LayerDev& ld = h->b.layers[l];
-    bf16_t* pool_l = h->pool + (size_t)l * h->layer_pool_elems;
+    kv_t* pool_l = h->pool + (size_t)l * h->layer_pool_elems;
     LAUNCH(h, st, HAT_K_RMSNORM,
            hat_launch_rmsnorm(h->b.resid, h->b.gemm_part, nparts, ld.g_attn, h->b.xn, T, s.d, c.rms_eps, st));
     nparts = 0;
@@ -830,10 +831,10 @@ static hat_status_t enqueue_step(hat_mid_t* h, const StepPlan& sp, const int32_t
     g.epilogue = HAT_EPI_P32;
     hat_status_t rc = run_gemm(HAT_K_GEMM_QKV, g, nullptr);
     if (rc != HAT_OK) return rc;
-    LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_append(pd, h->b.qkv, h->b.table, pool_l, c.n_pages, s.H, s.hd, st));
+    LAUNCH(h, st, HAT_K_ROPE_APPEND, hat_launch_rope_append(pd, h->b.qkv, h->b.table, pool_l, c.n_pages, s.H, s.hd, c.kv_dtype == HAT_KV_F16, st));
     HatAttn a{};
     a.qkv = h->b.qkv; a.pool_layer = pool_l; a.outP = h->b.attn; a.part_o = h->b.part_o; a.part_ml = h->b.part_ml;
-    a.H = s.H; a.hd = s.hd; a.d = s.d; a.n_pages = c.n_pages;
+    a.H = s.H; a.hd = s.hd; a.d = s.d; a.n_pages = c.n_pages; a.kv_f16 = c.kv_dtype == HAT_KV_F16;
     if (sp.n_citems > 0) {
       a.items = (const HatAttnItem*)(D + o_ci); a.n_items = sp.n_citems;
       LAUNCH(h, st, HAT_K_ATTN_CHUNK, hat_launch_attn_chunk(pd, a, st));
@@ -1040,7 +1041,7 @@ hat_status_t hat_mid_kv_import(hat_mid_t* h, int32_t device_id, int32_t layer, i
   hat_status_t rc = fixture_pages(h, d, pos0, n, st);
   if (rc == HAT_OK) {
     const hipError_t e = hat_launch_kv_import(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages,
-                                              pos0, n, (const bf16_t*)k, (const bf16_t*)v, c.n_heads, c.head_dim, st);
+                                              pos0, n, (const bf16_t*)k, (const bf16_t*)v, c.n_heads, c.head_dim, c.kv_dtype == HAT_KV_F16, st);
     if (e != hipSuccess) rc = fail(h, HAT_EHIP, "kv import launch failed: %s", hipGetErrorString(e));
   }
   if (rc != HAT_OK) {
@@ -1065,7 +1066,7 @@ hat_status_t hat_mid_kv_export(hat_mid_t* h, int32_t device_id, int32_t layer, i
   hat_status_t rc = fixture_pages(h, d, pos0, n, st);
   if (rc != HAT_OK) return rc;
   HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->b.fixture_pages, pos0, n,
-                                  (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, st));
+                                  (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, c.kv_dtype == HAT_KV_F16, st));
   return HAT_OK;
 }
 
@@ -1092,7 +1093,7 @@ hat_status_t hat_mid_kv_export_static(hat_mid_t* h, int32_t device_id, int32_t l
   HIP_TRY(h, hipEventRecord(h->static_ev, st));
   h->static_ev_used = true;
   HIP_TRY(h, hat_launch_kv_export(h->pool + (size_t)layer * h->layer_pool_elems, c.n_pages, h->static_pages_dev, pos0, n,
-                                  (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, st));
+                                  (bf16_t*)k, (bf16_t*)v, c.n_heads, c.head_dim, c.kv_dtype == HAT_KV_F16, st));
   return HAT_OK;
 }
 

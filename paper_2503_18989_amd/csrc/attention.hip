@@ -141,7 +141,10 @@ __device__ __forceinline__ f16x8 clean_v(f16x8 v, int page_key0, int half, int k
 // 8 bf16 (as loaded from the cache) -> 8 fp16.  bf16 -> fp32 is a shift; fp32 -> fp16
 // with round-toward-zero is exact where the value is representable and saturates
 // (instead of overflowing to infinity) where it is not.
+// With an fp16 cache (KVF16) the elements are operands as they are.
+template <bool KVF16>
 __device__ __forceinline__ u32x4 kv_to_f16_bits(u32x4 raw) {
+  if constexpr (KVF16) return raw;
   u32x4 out;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -150,12 +153,13 @@ __device__ __forceinline__ u32x4 kv_to_f16_bits(u32x4 raw) {
   }
   return out;
 }
-__device__ __forceinline__ f16x8 kv_to_f16(u32x4 raw) { return __builtin_bit_cast(f16x8, kv_to_f16_bits(raw)); }
+template <bool KVF16>
+__device__ __forceinline__ f16x8 kv_to_f16(u32x4 raw) { return __builtin_bit_cast(f16x8, kv_to_f16_bits<KVF16>(raw)); }
 
 __device__ __forceinline__ _Float16 to_act(float x) { return (_Float16)__builtin_amdgcn_fmed3f(x, -65504.f, 65504.f); }
 
 // ------------------------------------------------------------------ verify
-template <int HD>
+template <int HD, bool KVF16>
 __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAttn a) {
   constexpr int NS = HD / 16;  // k-steps of Q K^T
   constexpr int NC = HD / 32;  // 32-row blocks of O^T
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
 
   int kv_end = it.kv_end < sg.kv_len ? it.kv_end : sg.kv_len;
   const int pair0 = it.kv_begin >> 5, pair1 = (kv_end + 31) >> 5;
-  const bf16_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
+  const kv_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
   const size_t page_stride = REC;
 
   // One register stage of raw page data per wave, refilled as early as possible: the loads of
@@ -195,7 +199,7 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
   // raw registers, and travel while the current pair is soft-maxed and multiplied.  Two
   // workgroups share a CU (<= 256 VGPRs).
   u32x4 kraw[NS], varaw[NC], vbraw[NC];
-  const bf16_t *recA = pool, *recB = pool;
+  const kv_t *recA = pool, *recB = pool;
   auto page_recs = [&](int pp) {   // wave-uniform: scalar loads of the two page ids
     int ia = 2 * pp, ib = 2 * pp + 1;
     ib = ib < sg.npages ? ib : sg.npages - 1;
@@ -203,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
     recB = pool + (size_t)sg.pt[ib] * page_stride;
   };
   auto load_k = [&]() {
-    const bf16_t* krec = (n < 16) ? recA : recB;
+    const kv_t* krec = (n < 16) ? recA : recB;
 #pragma unroll
     for (int s = 0; s < NS; ++s) kraw[s] = stream_load((const u32x4*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8));
   };
@@ -226,12 +230,12 @@ __global__ __launch_bounds__(256, 2) void attn_verify_kernel(HatPlanDev p, HatAt
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kv_to_f16(kraw[s]), qreg[s], sacc, 0, 0, 0);
+    for (int s = 0; s < NS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kv_to_f16<KVF16>(kraw[s]), qreg[s], sacc, 0, 0, 0);
     f16x8 va[NC], vb[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      va[c] = kv_to_f16(varaw[c]);
-      vb[c] = kv_to_f16(vbraw[c]);
+      va[c] = kv_to_f16<KVF16>(varaw[c]);
+      vb[c] = kv_to_f16<KVF16>(vbraw[c]);
     }
     if (pp + 4 < pair1) {
       page_recs(pp + 4);
@@ -326,10 +330,10 @@ __global__ __launch_bounds__(256, 2) void attn_verify_probe_kernel(HatPlanDev p,
   const int half = lane >> 5, n = lane & 31;
   int kv_end = it.kv_end < sg.kv_len ? it.kv_end : sg.kv_len;
   const int pair0 = it.kv_begin >> 5, pair1 = (kv_end + 31) >> 5;
-  const bf16_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;
+  const kv_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;
   u32x4 acc = {0, 0, 0, 0};
   u32x4 kraw[NS], varaw[NC], vbraw[NC];
-  const bf16_t *recA = pool, *recB = pool;
+  const kv_t *recA = pool, *recB = pool;
   auto page_recs = [&](int pp) {
     int ia = 2 * pp, ib = 2 * pp + 1;
     ib = ib < sg.npages ? ib : sg.npages - 1;
@@ -337,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void attn_verify_probe_kernel(HatPlanDev p,
     recB = pool + (size_t)sg.pt[ib] * REC;
   };
   auto load_all = [&]() {
-    const bf16_t* krec = (n < 16) ? recA : recB;
+    const kv_t* krec = (n < 16) ? recA : recB;
 #pragma unroll
     for (int s = 0; s < NS; ++s) kraw[s] = stream_load((const u32x4*)(krec + ((2 * s + half) * 16 + (n & 15)) * 8));
 #pragma unroll
@@ -392,7 +396,7 @@ __device__ __forceinline__ void probs_to_f16(const f32x16& pv, f16x8& p0, f16x8&
   }
 }
 
-template <int HD>
+template <int HD, bool KVF16>
 __global__ __launch_bounds__(HAT_CHUNK_QROWS * 2) void attn_chunk_kernel(HatPlanDev p, HatAttn a) {
   constexpr int NS = HD / 16;
   constexpr int NC = HD / 32;
@@ -437,7 +441,7 @@ __global__ __launch_bounds__(HAT_CHUNK_QROWS * 2) void attn_chunk_kernel(HatPlan
   const int need = sg.start + it.q0 + it.nq;
   kv_end = kv_end < need ? kv_end : need;
   const int st0 = it.kv_begin >> 6, st1 = (kv_end + 63) >> 6;
-  const bf16_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
+  const kv_t* pool = a.pool_layer + (size_t)head * a.n_pages * REC;  // this head's pages are contiguous
   const size_t page_stride = REC;
 
   // K/V stages travel global -> registers -> (widen to fp16) -> LDS.  The loads of stage
@@ -479,7 +483,7 @@ __global__ __launch_bounds__(HAT_CHUNK_QROWS * 2) void attn_chunk_kernel(HatPlan
   };
   auto lstore = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * NTH + threadIdx.x) * 16]) = kv_to_f16_bits(regs[i]);
+    for (int i = 0; i < LPT; ++i) *(u32x4*)(&lds[buf][(i * NTH + threadIdx.x) * 16]) = kv_to_f16_bits<KVF16>(regs[i]);
   };
   // general stage: causal masks, ragged ends, waves that skip a 32-key half
   auto compute = [&](int st, int buf) {
@@ -618,7 +622,7 @@ __global__ __launch_bounds__(HAT_CHUNK_QROWS * 2) void attn_chunk_kernel(HatPlan
         if constexpr (m < NS) {                                  // scores of A | widen next stage into LDS
           sA = __builtin_amdgcn_mfma_f32_32x32x16_f16(op[cur][j], qreg[m], m == 0 ? zero16 : sA, 0, 0, 0);
           if constexpr (m < LPT) {
-            if (do_store) *(u32x4*)(&lds[buf ^ 1][(m * NTH + threadIdx.x) * 16]) = kv_to_f16_bits(regs[m]);
+            if (do_store) *(u32x4*)(&lds[buf ^ 1][(m * NTH + threadIdx.x) * 16]) = kv_to_f16_bits<KVF16>(regs[m]);
           }
         } else if constexpr (m < 2 * NS) {                       // scores of B | loads of stage st+2, softmax of A
           constexpr int q = m - NS;
@@ -732,8 +736,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(HatAttn a, const HatMer
 hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStream_t st) {
   if (a.n_items <= 0) return hipSuccess;
   dim3 grid(a.n_items, a.H);
-  if (a.hd == 128) attn_chunk_kernel<128><<<grid, HAT_CHUNK_QROWS * 2, 0, st>>>(p, a);
-  else if (a.hd == 64) attn_chunk_kernel<64><<<grid, HAT_CHUNK_QROWS * 2, 0, st>>>(p, a);
+  if (a.hd == 128 && a.kv_f16) attn_chunk_kernel<128, true><<<grid, HAT_CHUNK_QROWS * 2, 0, st>>>(p, a);
+  else if (a.hd == 128) attn_chunk_kernel<128, false><<<grid, HAT_CHUNK_QROWS * 2, 0, st>>>(p, a);
+  else if (a.hd == 64 && a.kv_f16) attn_chunk_kernel<64, true><<<grid, HAT_CHUNK_QROWS * 2, 0, st>>>(p, a);
+  else if (a.hd == 64) attn_chunk_kernel<64, false><<<grid, HAT_CHUNK_QROWS * 2, 0, st>>>(p, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
@@ -741,8 +747,10 @@ hipError_t hat_launch_attn_chunk(const HatPlanDev& p, const HatAttn& a, hipStrea
 hipError_t hat_launch_attn_verify(const HatPlanDev& p, const HatAttn& a, hipStream_t st) {
   if (a.n_items <= 0) return hipSuccess;
   dim3 grid(a.n_items, a.H);
-  if (a.hd == 128) attn_verify_kernel<128><<<grid, 256, 0, st>>>(p, a);
-  else if (a.hd == 64) attn_verify_kernel<64><<<grid, 256, 0, st>>>(p, a);
+  if (a.hd == 128 && a.kv_f16) attn_verify_kernel<128, true><<<grid, 256, 0, st>>>(p, a);
+  else if (a.hd == 128) attn_verify_kernel<128, false><<<grid, 256, 0, st>>>(p, a);
+  else if (a.hd == 64 && a.kv_f16) attn_verify_kernel<64, true><<<grid, 256, 0, st>>>(p, a);
+  else if (a.hd == 64) attn_verify_kernel<64, false><<<grid, 256, 0, st>>>(p, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -15,6 +15,33 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ _Float16 to_act(float x) { return (_Float16)__builtin_amdgcn_fmed3f(x, -65504.f, 65504.f); }
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t kvx8 __attribute__((ext_vector_type(8)));
+
+// eight values -> eight cache elements: bf16 (round to nearest even) or fp16 (the same, saturating)
+template <bool KVF16>
+__device__ __forceinline__ kvx8 to_kv(const float (&x)[8]) {
+  if constexpr (KVF16) {
+    f16x8 h;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = to_act(x[e]);
+    return __builtin_bit_cast(kvx8, h);
+  } else {
+    bf16x8 b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[e] = (__bf16)x[e];
+    return __builtin_bit_cast(kvx8, b);
+  }
+}
+template <bool KVF16>
+__device__ __forceinline__ float kv_to_float(kv_t x) {
+  if constexpr (KVF16) return (float)__builtin_bit_cast(_Float16, x);
+  else return (float)__builtin_bit_cast(__bf16, x);
+}
+template <bool KVF16>
+__device__ __forceinline__ kv_t float_to_kv(float x) {
+  if constexpr (KVF16) return __builtin_bit_cast(kv_t, to_act(x));
+  else return __builtin_bit_cast(kv_t, (__bf16)x);
+}
 
 namespace {
 
@@ -141,8 +168,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ resid,
 //      rows whose slots share a lane half, transposes in registers and writes, per
 //      feature, the 8 slots as one 16-byte run of the V tile (whose order is
 //      [feature][slot]); slots that are not new in this step keep their old contents.
+template <bool KVF16>
 __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const float2* __restrict__ table,
-                                   bf16_t* __restrict__ pool, int n_pages, int H, int hd) {
+                                   kv_t* __restrict__ pool, int n_pages, int H, int hd) {
   const int half_oct = hd >> 4;                 // octets per half head
   const int per_row = H * half_oct;
   const int n_a = p.T * per_row;
@@ -162,7 +190,7 @@ __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const 
     const f16x8 kl = *(const f16x8*)(qkv + p32_index(t, d + c_lo, row_len));
     const f16x8 kh = *(const f16x8*)(qkv + p32_index(t, d + c_hi, row_len));
     f16x8 rql, rqh;
-    bf16x8 rkl, rkh;
+    float rkl[8], rkh[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float c = cs[e].x, s = cs[e].y;
@@ -170,16 +198,16 @@ __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const 
       rql[e] = to_act(a * c - b * s);
       rqh[e] = to_act(b * c + a * s);
       const float ka = (float)kl[e], kb = (float)kh[e];
-      rkl[e] = (__bf16)(ka * c - kb * s);
-      rkh[e] = (__bf16)(kb * c + ka * s);
+      rkl[e] = ka * c - kb * s;
+      rkh[e] = kb * c + ka * s;
     }
     *(f16x8*)q_lo = rql;
     *(f16x8*)q_hi = rqh;
     const int dst = p.kv_dst[t];
     const int page = dst >> 4, slot = dst & 15;
-    bf16_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
-    *(bf16x8*)(kt + ktile_index(slot, o * 8)) = rkl;
-    *(bf16x8*)(kt + ktile_index(slot, o * 8 + (hd >> 1))) = rkh;
+    kv_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
+    *(kvx8*)(kt + ktile_index(slot, o * 8)) = to_kv<KVF16>(rkl);
+    *(kvx8*)(kt + ktile_index(slot, o * 8 + (hd >> 1))) = to_kv<KVF16>(rkh);
     return;
   }
   const int octs = hd >> 3;
@@ -190,7 +218,7 @@ __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const 
   const int o = vrem % octs;
   const int half = (vrem / octs) & 1;
   const int hh = vrem / (2 * octs);
-  bf16_t* vt = pool + ((size_t)hh * n_pages + it.page) * kv_head_elems(hd) + 16 * hd;
+  kv_t* vt = pool + ((size_t)hh * n_pages + it.page) * kv_head_elems(hd) + 16 * hd;
   f16x8 rows[8];
   bool valid[8];
   bool all = true;
@@ -204,13 +232,16 @@ __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const 
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    bf16_t* dst = vt + vtile_index(4 * half, o * 8 + e);   // j = 0 of this half: 8 slots follow contiguously
-    bf16x8 out;
-    if (!all) out = *(const bf16x8*)dst;
+    kv_t* dst = vt + vtile_index(4 * half, o * 8 + e);   // j = 0 of this half: 8 slots follow contiguously
+    kvx8 out;
+    if (!all) out = *(const kvx8*)dst;
 #pragma unroll
     for (int j = 0; j < 8; ++j)
-      if (valid[j]) out[j] = (__bf16)(float)rows[j][e];
-    *(bf16x8*)dst = out;
+      if (valid[j]) {
+        const _Float16 x = rows[j][e];   // (a copy: bit_cast must not be handed the vector element itself)
+        out[j] = KVF16 ? __builtin_bit_cast(kv_t, x) : float_to_kv<false>((float)x);
+      }
+    *(kvx8*)dst = out;
   }
 }
 
@@ -271,7 +302,8 @@ __global__ void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __rest
 
 // ---------------------------------------------------------------- fixtures
 // one thread per (row, head, octet)
-__global__ void kv_import_kernel(bf16_t* __restrict__ pool, int n_pages, const int32_t* __restrict__ pages, int pos0, int n,
+template <bool KVF16>
+__global__ void kv_import_kernel(kv_t* __restrict__ pool, int n_pages, const int32_t* __restrict__ pages, int pos0, int n,
                                  const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int H, int hd) {
   const int octs = hd >> 3;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -281,16 +313,21 @@ __global__ void kv_import_kernel(bf16_t* __restrict__ pool, int n_pages, const i
   const int r = (int)(idx / ((size_t)octs * H));
   const int pos = pos0 + r;
   const int page = pages[(pos >> 4) - (pos0 >> 4)], slot = pos & 15;
-  bf16_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
-  bf16_t* vt = kt + 16 * hd;
+  kv_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
+  kv_t* vt = kt + 16 * hd;
   const size_t so = ((size_t)r * H + hh) * hd + o * 8;
-  *(bf16x8*)(kt + ktile_index(slot, o * 8)) = *(const bf16x8*)(k + so);
+  const bf16x8 kk = *(const bf16x8*)(k + so);
   const bf16x8 vv = *(const bf16x8*)(v + so);
+  float kf[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) vt[vtile_index(slot, o * 8 + e)] = vv[e];
+  for (int e = 0; e < 8; ++e) kf[e] = (float)kk[e];
+  *(kvx8*)(kt + ktile_index(slot, o * 8)) = to_kv<KVF16>(kf);      // bf16 -> bf16 is the identity
+#pragma unroll
+  for (int e = 0; e < 8; ++e) vt[vtile_index(slot, o * 8 + e)] = float_to_kv<KVF16>((float)vv[e]);
 }
 
-__global__ void kv_export_kernel(const bf16_t* __restrict__ pool, int n_pages, const int32_t* __restrict__ pages, int pos0, int n,
+template <bool KVF16>
+__global__ void kv_export_kernel(const kv_t* __restrict__ pool, int n_pages, const int32_t* __restrict__ pages, int pos0, int n,
                                  bf16_t* __restrict__ k, bf16_t* __restrict__ v, int H, int hd) {
   const int octs = hd >> 3;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -300,20 +337,24 @@ __global__ void kv_export_kernel(const bf16_t* __restrict__ pool, int n_pages, c
   const int r = (int)(idx / ((size_t)octs * H));
   const int pos = pos0 + r;
   const int page = pages[(pos >> 4) - (pos0 >> 4)], slot = pos & 15;
-  const bf16_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
-  const bf16_t* vt = kt + 16 * hd;
+  const kv_t* kt = pool + ((size_t)hh * n_pages + page) * kv_head_elems(hd);
+  const kv_t* vt = kt + 16 * hd;
   const size_t so = ((size_t)r * H + hh) * hd + o * 8;
-  *(bf16x8*)(k + so) = *(const bf16x8*)(kt + ktile_index(slot, o * 8));
-  bf16x8 vv;
+  const kvx8 kk = *(const kvx8*)(kt + ktile_index(slot, o * 8));
+  bf16x8 ko, vv;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) vv[e] = vt[vtile_index(slot, o * 8 + e)];
+  for (int e = 0; e < 8; ++e) {
+    ko[e] = (__bf16)kv_to_float<KVF16>(kk[e]);
+    vv[e] = (__bf16)kv_to_float<KVF16>(vt[vtile_index(slot, o * 8 + e)]);
+  }
+  *(bf16x8*)(k + so) = ko;
   *(bf16x8*)(v + so) = vv;
 }
 
 // One thread per (layer, head, octet of the head): applies the row moves in order.  The moves
 // of a kept tree path go to lower-or-equal rows in ascending order, so a destination is never a
 // source of a later move, and no two threads touch the same bytes.
-__global__ void kv_move_kernel(bf16_t* __restrict__ pool, size_t layer_elems, int L, int n_pages, HatRowMoves mv, int H,
+__global__ void kv_move_kernel(kv_t* __restrict__ pool, size_t layer_elems, int L, int n_pages, HatRowMoves mv, int H,
                                int hd) {
   const int octs = hd >> 3;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -321,12 +362,12 @@ __global__ void kv_move_kernel(bf16_t* __restrict__ pool, size_t layer_elems, in
   const int o = (int)(idx % octs);
   const int hh = (int)((idx / octs) % H);
   const int l = (int)(idx / ((size_t)octs * H));
-  bf16_t* base = pool + (size_t)l * layer_elems + (size_t)hh * n_pages * kv_head_elems(hd);
+  kv_t* base = pool + (size_t)l * layer_elems + (size_t)hh * n_pages * kv_head_elems(hd);
   for (int m = 0; m < mv.n; ++m) {
-    bf16_t* sp = base + (size_t)(mv.src[m] >> 4) * kv_head_elems(hd);
-    bf16_t* dp = base + (size_t)(mv.dst[m] >> 4) * kv_head_elems(hd);
+    kv_t* sp = base + (size_t)(mv.src[m] >> 4) * kv_head_elems(hd);
+    kv_t* dp = base + (size_t)(mv.dst[m] >> 4) * kv_head_elems(hd);
     const int ss = mv.src[m] & 15, ds = mv.dst[m] & 15;
-    *(bf16x8*)(dp + ktile_index(ds, o * 8)) = *(const bf16x8*)(sp + ktile_index(ss, o * 8));
+    *(kvx8*)(dp + ktile_index(ds, o * 8)) = *(const kvx8*)(sp + ktile_index(ss, o * 8));
 #pragma unroll
     for (int e = 0; e < 8; ++e) dp[16 * hd + vtile_index(ds, o * 8 + e)] = sp[16 * hd + vtile_index(ss, o * 8 + e)];
   }
@@ -364,10 +405,11 @@ hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const
   rmsnorm_kernel<<<T, 256, 0, st>>>(resid, part, nparts, T, gain, outP, d, eps);
   return hipGetLastError();
 }
-hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, bf16_t* pool_layer,
-                                  int n_pages, int H, int hd, hipStream_t st) {
+hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, kv_t* pool_layer,
+                                  int n_pages, int H, int hd, int kv_f16, hipStream_t st) {
   const size_t n = (size_t)p.T * H * (hd >> 4) + (size_t)p.n_append * H * 2 * (hd >> 3);
-  rope_append_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, hd);
+  if (kv_f16) rope_append_kernel<true><<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, hd);
+  else rope_append_kernel<false><<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, hd);
   return hipGetLastError();
 }
 hipError_t hat_launch_retile(act_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1, const bf16_t* src2,
@@ -380,19 +422,21 @@ hipError_t hat_launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStrea
   bf16_to_f32_kernel<<<blocks_for(n, 256), 256, 0, st>>>(src, dst, n);
   return hipGetLastError();
 }
-hipError_t hat_launch_kv_import(bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
-                                const bf16_t* k, const bf16_t* v, int H, int hd, hipStream_t st) {
+hipError_t hat_launch_kv_import(kv_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
+                                const bf16_t* k, const bf16_t* v, int H, int hd, int kv_f16, hipStream_t st) {
   const size_t cnt = (size_t)n * H * (hd >> 3);
-  kv_import_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
+  if (kv_f16) kv_import_kernel<true><<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
+  else kv_import_kernel<false><<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
   return hipGetLastError();
 }
-hipError_t hat_launch_kv_export(const bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
-                                bf16_t* k, bf16_t* v, int H, int hd, hipStream_t st) {
+hipError_t hat_launch_kv_export(const kv_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
+                                bf16_t* k, bf16_t* v, int H, int hd, int kv_f16, hipStream_t st) {
   const size_t cnt = (size_t)n * H * (hd >> 3);
-  kv_export_kernel<<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
+  if (kv_f16) kv_export_kernel<true><<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
+  else kv_export_kernel<false><<<blocks_for(cnt, 256), 256, 0, st>>>(pool_layer, n_pages, pages, pos0, n, k, v, H, hd);
   return hipGetLastError();
 }
-hipError_t hat_launch_kv_move(bf16_t* pool, size_t layer_elems, int L, int n_pages, const HatRowMoves& mv, int H,
+hipError_t hat_launch_kv_move(kv_t* pool, size_t layer_elems, int L, int n_pages, const HatRowMoves& mv, int H,
                               int hd, hipStream_t st) {
   if (mv.n <= 0) return hipSuccess;
   const size_t cnt = (size_t)L * H * (hd >> 3);

@@ -5,8 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-typedef __bf16 bf16_t;    // storage type of the callers' weights, of hidden in/out and of the KV cache
+typedef __bf16 bf16_t;    // storage type of the callers' weights, of hidden in/out and of imported / exported cache rows
 typedef _Float16 act_t;   // arithmetic type of the MFMA operands: re-tiled weights and all activations
+typedef uint16_t kv_t;    // one KV-cache element: bf16 or fp16 bits, as the handle's configuration says (kv_f16)
 
 constexpr int HAT_MAX_VERIFY_ROWS = 8;  // query rows of a verify work item
 // query rows of one chunk-attention workgroup: 8 waves x 32 rows (the 64-key K/V stage that a
@@ -88,8 +89,8 @@ hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, fl
 hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, act_t* outP, int T,
                               int d, float eps, hipStream_t st);
 // qkv: P32 [., 3d]; rotates q in place, writes rotated k and v into the pool of one layer
-hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, bf16_t* pool_layer,
-                                  int n_pages, int H, int hd, hipStream_t st);
+hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, kv_t* pool_layer,
+                                  int n_pages, int H, int hd, int kv_f16, hipStream_t st);
 
 // ---- attention ---------------------------------------------------------------
 // One work item = 32*QB query rows of one segment against keys [kv_begin, kv_end).
@@ -120,7 +121,8 @@ struct HatMergeItem {
 };
 struct HatAttn {
   const act_t* qkv;          // P32 [., 3d]; q = columns [0, d)
-  const bf16_t* pool_layer;  // this layer's pages
+  const kv_t* pool_layer;    // this layer's pages
+  int kv_f16;                // cache elements are fp16 (else bf16, widened to fp16 on their way to the MFMA)
   act_t* outP;               // P32 [., d]
   act_t* part_o;             // [part rows][H][hd] partial outputs, each normalised by its own sum
   float2* part_ml;           // [part rows][H] (running max in log2 units, sum)
@@ -136,18 +138,19 @@ hipError_t hat_launch_attn_merge(const HatAttn& a, const HatMergeItem* items, in
 hipError_t hat_launch_attn_verify_probe(const HatPlanDev& p, const HatAttn& a, uint32_t* sink, hipStream_t st);
 
 // ---- fixtures ------------------------------------------------------------------
-// k, v: [n, H, hd] bf16 plain; pages: device array of the page ids covering the rows
-hipError_t hat_launch_kv_import(bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
-                                const bf16_t* k, const bf16_t* v, int H, int hd, hipStream_t st);
+// k, v: [n, H, hd] bf16 plain; pages: device array of the page ids covering the rows.  An fp16 cache
+// takes the bf16 values exactly (where fp16 can hold them) and gives them back rounded to bf16.
+hipError_t hat_launch_kv_import(kv_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
+                                const bf16_t* k, const bf16_t* v, int H, int hd, int kv_f16, hipStream_t st);
 // Row moves inside one device's cache, applied in order in every layer and head.
 struct HatRowMoves {
   int32_t n;
   int32_t src[HAT_MAX_VERIFY_ROWS], dst[HAT_MAX_VERIFY_ROWS];  // page*16 + slot
 };
-hipError_t hat_launch_kv_move(bf16_t* pool, size_t layer_elems, int L, int n_pages, const HatRowMoves& mv, int H,
+hipError_t hat_launch_kv_move(kv_t* pool, size_t layer_elems, int L, int n_pages, const HatRowMoves& mv, int H,
                               int hd, hipStream_t st);
-hipError_t hat_launch_kv_export(const bf16_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
-                                bf16_t* k, bf16_t* v, int H, int hd, hipStream_t st);
+hipError_t hat_launch_kv_export(const kv_t* pool_layer, int n_pages, const int32_t* pages, int pos0, int n,
+                                bf16_t* k, bf16_t* v, int H, int hd, int kv_f16, hipStream_t st);
 // P32 [., ncols_total] columns [col0, col0+ncols) -> fp32 row-major [T, ncols]
 hipError_t hat_launch_unpack_p32(const act_t* srcP, int row_len, int col0, int ncols, int T, float* dst,
                                  hipStream_t st);

@@ -129,6 +129,7 @@ class Pair:
 
     def close(self):
         if hasattr(self, "worst_rel"):
-            progress("%s (%d layers, %s io): worst rel %.3e, worst vs added %.3e"
-                     % (self.cfg.get("name", "?"), self.cfg["n_layers"], self.io_dtype, self.worst_rel, self.worst_added))
+            progress("%s (%d layers, %s io, %s cache): worst rel %.3e, worst vs added %.3e"
+                     % (self.cfg.get("name", "?"), self.cfg["n_layers"], self.io_dtype, getattr(self.gpu, "kv_dtype", "?"),
+                        self.worst_rel, self.worst_added))
         self.gpu.close()

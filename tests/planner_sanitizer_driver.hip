@@ -20,14 +20,14 @@ hipError_t hat_launch_gather(const HatPlanDev&, float*, int, int, hipStream_t) {
 hipError_t hat_launch_scatter(const HatPlanDev&, const float*, const float*, int, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_rope_table(const HatPlanDev&, const double*, float2*, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_rmsnorm(float*, const float*, int, const float*, act_t*, int, int, float, hipStream_t) { return hipErrorUnknown; }
-hipError_t hat_launch_rope_append(const HatPlanDev&, act_t*, const float2*, bf16_t*, int, int, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t hat_launch_rope_append(const HatPlanDev&, act_t*, const float2*, kv_t*, int, int, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_attn_chunk(const HatPlanDev&, const HatAttn&, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_attn_verify(const HatPlanDev&, const HatAttn&, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_attn_merge(const HatAttn&, const HatMergeItem*, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_attn_verify_probe(const HatPlanDev&, const HatAttn&, uint32_t*, hipStream_t) { return hipErrorUnknown; }
-hipError_t hat_launch_kv_import(bf16_t*, int, const int32_t*, int, int, const bf16_t*, const bf16_t*, int, int, hipStream_t) { return hipErrorUnknown; }
-hipError_t hat_launch_kv_move(bf16_t*, size_t, int, int, const HatRowMoves&, int, int, hipStream_t) { return hipErrorUnknown; }
-hipError_t hat_launch_kv_export(const bf16_t*, int, const int32_t*, int, int, bf16_t*, bf16_t*, int, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t hat_launch_kv_import(kv_t*, int, const int32_t*, int, int, const bf16_t*, const bf16_t*, int, int, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t hat_launch_kv_move(kv_t*, size_t, int, int, const HatRowMoves&, int, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t hat_launch_kv_export(const kv_t*, int, const int32_t*, int, int, bf16_t*, bf16_t*, int, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_unpack_p32(const act_t*, int, int, int, int, float*, hipStream_t) { return hipErrorUnknown; }
 
 #define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "check failed: %s (line %d)\n", #c, __LINE__); return 1; } } while (0)

@@ -32,8 +32,12 @@ def check(outs, refs, tol=TOL):
         assert e <= tol, "rel err %.3e (l2 %.3e)" % (e, rel_l2(o, r))
 
 
-def test_tiny_workload_full_parity_and_pages():
-    p = Pair(hi.TINY, 1000, n_pages=16, gain_jitter=0.0, max_devices=4, max_step_tokens=64, max_pos=256)
+KV = pytest.mark.parametrize("kv", ["bf16", "f16"])     # element type of the cache: the workloads' bf16, and fp16
+
+
+@KV
+def test_tiny_workload_full_parity_and_pages(kv):
+    p = Pair(hi.TINY, 1000, n_pages=16, gain_jitter=0.0, max_devices=4, max_step_tokens=64, max_pos=256, kv_dtype=kv)
     for step in hi.tiny_schedule():
         outs, refs = p.step(step)
         check(outs, refs)
@@ -160,9 +164,10 @@ def test_every_gemm_tile_forced(T):
     p.close()
 
 
+@KV
 @pytest.mark.parametrize("cfg", [SMALL64, SMALL128], ids=["hd64", "hd128"])
-def test_mixed_ragged_batches_with_rollback(cfg):
-    p = Pair(cfg, 21, n_pages=200, max_devices=8, max_step_tokens=1024, max_pos=2048)
+def test_mixed_ragged_batches_with_rollback(cfg, kv):
+    p = Pair(cfg, 21, n_pages=200, max_devices=8, max_step_tokens=1024, max_pos=2048, kv_dtype=kv)
     ln = {}
 
     def run(segs):
@@ -180,11 +185,12 @@ def test_mixed_ragged_batches_with_rollback(cfg):
     p.close()
 
 
+@KV
 @pytest.mark.parametrize("target", [64, 4096])
-def test_split_kv_paths_long_cache(target):
+def test_split_kv_paths_long_cache(target, kv):
     # a large work-group target forces the key range of both attention kernels to be
     # split over several work-groups and merged; a small one keeps them whole
-    p = Pair(SMALL128, 31, n_pages=160, max_devices=4, max_step_tokens=2048, max_pos=4096)
+    p = Pair(SMALL128, 31, n_pages=160, max_devices=4, max_step_tokens=2048, max_pos=4096, kv_dtype=kv)
     p.gpu.set_attn_targets(target, target)
     outs, refs = p.step([(0, hi.CHUNK, 0, 700), (1, hi.CHUNK, 0, 1000)])
     check(outs, refs)
@@ -215,9 +221,10 @@ def test_chunked_equals_unchunked_on_gpu_and_f32_io():
     a.close(); b.close()
 
 
-def test_kv_import_export_roundtrip_and_attention_over_imported_prefix():
+@KV
+def test_kv_import_export_roundtrip_and_attention_over_imported_prefix(kv):
     cfg = SMALL128
-    p = Pair(cfg, 51, n_pages=100, max_devices=4, max_step_tokens=256, max_pos=2048)
+    p = Pair(cfg, 51, n_pages=100, max_devices=4, max_step_tokens=256, max_pos=2048, kv_dtype=kv)
     H, hd = cfg["n_heads"], cfg["head_dim"]
     n = 333
     for l in range(cfg["n_layers"]):
@@ -225,7 +232,13 @@ def test_kv_import_export_roundtrip_and_attention_over_imported_prefix():
         p.gpu.kv_import(2, l, 0, to_dev_bf16(k).view(n, H, hd), to_dev_bf16(v).view(n, H, hd))
         p.ref.import_kv(2, l, 0, k, v)
         ke, ve = p.gpu.kv_export(2, l, 0, n)
-        assert np.array_equal(to_np(ke), k) and np.array_equal(to_np(ve), v)   # byte-exact round trip
+        if kv == "bf16":
+            assert np.array_equal(to_np(ke), k) and np.array_equal(to_np(ve), v)   # byte-exact round trip
+        else:     # an fp16 cache holds bf16 values exactly down to 2^-17; below that to within 2^-25
+            big = np.abs(k) >= 2.0 ** -17
+            assert np.array_equal(to_np(ke)[big], k[big]) and np.max(np.abs(to_np(ke) - k)) <= 2.0 ** -25
+            big = np.abs(v) >= 2.0 ** -17
+            assert np.array_equal(to_np(ve)[big], v[big]) and np.max(np.abs(to_np(ve) - v)) <= 2.0 ** -25
     # the page model sees an import as a chunk-like allocation
     p.pages.step([(2, 0, 0, 200)]); p.pages.step([(2, 0, 200, n - 200)])
     p.check_pages([2])
@@ -343,14 +356,15 @@ def test_host_fed_steps_equal_device_fed_steps(pinned):
     a.close(); b.close()
 
 
-@pytest.mark.parametrize("cfg,seed", [(SMALL128, 5), (SMALL64, 6)], ids=["hd128", "hd64"])
-def test_randomized_schedules(cfg, seed):
+@pytest.mark.parametrize("cfg,seed,kv", [(SMALL128, 5, "bf16"), (SMALL64, 6, "bf16"), (SMALL128, 7, "f16"), (SMALL64, 8, "f16")],
+                         ids=["hd128", "hd64", "hd128-f16kv", "hd64-f16kv"])
+def test_randomized_schedules(cfg, seed, kv):
     # seeded random mixes of chunks (1..600 rows), verify segments (1..8 rows, with rollback of 0..4
     # rows first), departures and re-joins over 6 devices: every step against the oracle, page tables
     # against the page model
     rng = np.random.default_rng(seed)
     ndev, max_pos, max_step = 6, 2048, 1024
-    p = Pair(cfg, 90 + seed, n_pages=6 * 2048 // 16 + 8, max_devices=ndev, max_step_tokens=max_step, max_pos=max_pos)
+    p = Pair(cfg, 90 + seed, n_pages=6 * 2048 // 16 + 8, max_devices=ndev, max_step_tokens=max_step, max_pos=max_pos, kv_dtype=kv)
     ln = [0] * ndev
     for step in range(36):
         segs, rows = [], 0
@@ -399,13 +413,14 @@ def test_widths_that_are_not_multiples_of_the_tiles(cfg):
     p.close()
 
 
-def test_positions_beyond_twenty_thousand():
+@KV
+def test_positions_beyond_twenty_thousand(kv):
     # a 20 000-row cache installed by import, then a 200-row chunk, a chain and a tree at positions
     # 20 000+: rotary angles of thousands of radians, a page list of 1 260 entries, 300+ key stages
     import torch
     cfg = dict(SMALL128, n_layers=1)
     H, hd = cfg["n_heads"], cfg["head_dim"]
-    p = Pair(cfg, 81, n_pages=2 * 20320 // 16 + 8, max_devices=2, max_step_tokens=256, max_pos=20400)
+    p = Pair(cfg, 81, n_pages=2 * 20320 // 16 + 8, max_devices=2, max_step_tokens=256, max_pos=20400, kv_dtype=kv)
     for dev in (0, 1):
         k, v = hi.kv_prefix(20000, H, hd, 81, dev, 0)
         p.gpu.kv_import(dev, 0, 0, to_dev_bf16(k).view(-1, H, hd), to_dev_bf16(v).view(-1, H, hd))
@@ -446,14 +461,15 @@ def test_sixty_four_devices_in_one_step():
     p.close()
 
 
-def test_results_are_bitwise_reproducible():
+@KV
+def test_results_are_bitwise_reproducible(kv):
     # split-K and split-KV reductions run in a fixed order (no atomics): two handles given the same
     # steps -- long enough for both kinds of split -- return the same bits
     import torch
     from paper_2503_18989_amd import Segment
     outs = []
     for _ in range(2):
-        p = Pair(SMALL128, 83, n_pages=200, max_devices=4, max_step_tokens=1280, max_pos=2048)
+        p = Pair(SMALL128, 83, n_pages=200, max_devices=4, max_step_tokens=1280, max_pos=2048, kv_dtype=kv)
         xs = [to_dev_bf16(hi.hidden_rows(n, 512, 83, i)) for i, n in enumerate((900, 300, 8, 5))]
         a = p.gpu.forward([Segment(0, hi.CHUNK, 0, xs[0]), Segment(1, hi.CHUNK, 0, xs[1])])
         b = p.gpu.forward([Segment(0, hi.VERIFY, 900, xs[2], tree_mask=hi.tree_masks(hi.MEDUSA_LIKE_TREE)),

@@ -28,9 +28,10 @@ def tree(parents):
 
 
 @pytest.mark.parametrize("cfg", [SMALL64, SMALL128], ids=["hd64", "hd128"])
-def test_tree_steps_compaction_and_what_follows(cfg):
+@pytest.mark.parametrize("kv", ["bf16", "f16"])
+def test_tree_steps_compaction_and_what_follows(cfg, kv):
     import torch
-    p = Pair(cfg, 41, n_pages=120, max_devices=8, max_step_tokens=512, max_pos=1024)
+    p = Pair(cfg, 41, n_pages=120, max_devices=8, max_step_tokens=512, max_pos=1024, kv_dtype=kv)
     # prefixes chosen so that the 8 tree rows end a page (8..15), straddle pages (28..35, 253..260),
     # start a page (64..) and start the cache (device 4: no prefix at all)
     check(*p.step([(0, hi.CHUNK, 0, 28), (1, hi.CHUNK, 0, 8), (2, hi.CHUNK, 0, 253), (3, hi.CHUNK, 0, 64)]))
@@ -155,10 +156,11 @@ def test_tree_and_compact_errors_are_atomic():
 
 
 @pytest.mark.parametrize("start", [0, 1, 8, 15, 16, 31])
-def test_verify_over_tiny_caches(start):
+@pytest.mark.parametrize("kv", ["bf16", "f16"])
+def test_verify_over_tiny_caches(start, kv):
     # with almost no prefix the segment's own rows carry all the attention weight, so a row that
     # failed to see them (or saw one too many) is far outside the bar -- a long prefix would hide it
-    p = Pair(SMALL64, 45, n_pages=8, max_devices=4, max_step_tokens=64, max_pos=64)
+    p = Pair(SMALL64, 45, n_pages=8, max_devices=4, max_step_tokens=64, max_pos=64, kv_dtype=kv)
     if start:
         check(*p.step([(0, hi.CHUNK, 0, start), (1, hi.CHUNK, 0, start)]))
     check(*p.step([(0, hi.VERIFY, start, 8), (1, hi.VERIFY, start, 8, tree(hi.MEDUSA_LIKE_TREE))]), tol=6e-3)

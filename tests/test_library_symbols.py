@@ -39,12 +39,12 @@ def test_library_exports_every_declared_symbol():
 def test_size_queries_reject_bad_configs_and_scale():
     from paper_2503_18989_amd.binding import load_library, Config
     lib = load_library()
-    good = Config(2, 256, 4, 64, 688, 1e-6, 1e4, 16, 10, 4, 64, 256, 0)
+    good = Config(2, 256, 4, 64, 688, 1e-6, 1e4, 16, 10, 4, 64, 256, 0, 0)
     kv = lib.hat_mid_kv_bytes(ctypes.byref(good))
     assert kv == 2 * 10 * 4 * 2 * 16 * 64 * 2
     assert lib.hat_mid_workspace_bytes(ctypes.byref(good)) > 0
-    for field, val in (("head_dim", 32), ("d_model", 250), ("page_size", 8), ("n_pages", 0), ("io_dtype", 7)):
-        bad = Config(2, 256, 4, 64, 688, 1e-6, 1e4, 16, 10, 4, 64, 256, 0)
+    for field, val in (("head_dim", 32), ("d_model", 250), ("page_size", 8), ("n_pages", 0), ("io_dtype", 7), ("kv_dtype", 2)):
+        bad = Config(2, 256, 4, 64, 688, 1e-6, 1e4, 16, 10, 4, 64, 256, 0, 0)
         setattr(bad, field, val)
         assert lib.hat_mid_kv_bytes(ctypes.byref(bad)) == 0
         assert lib.hat_mid_workspace_bytes(ctypes.byref(bad)) == 0
@@ -69,7 +69,7 @@ def test_headers_compile_as_plain_c99(tmp_path):
         pytest.skip("needs gcc")
     src = tmp_path / "abi.c"
     src.write_text('#include "hat_mid.h"\n#include "hat_sched.h"\n'
-                   'int main(void) { return (sizeof(hat_mid_segment_t) == 40 && sizeof(hat_mid_config_t) == 52) ? 0 : 1; }\n')
+                   'int main(void) { return (sizeof(hat_mid_segment_t) == 40 && sizeof(hat_mid_config_t) == 56) ? 0 : 1; }\n')
     exe = tmp_path / "abi"
     b = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
                         str(src), "-o", str(exe)], capture_output=True, text=True)
@@ -77,4 +77,4 @@ def test_headers_compile_as_plain_c99(tmp_path):
     assert subprocess.run([str(exe)]).returncode == 0
     from paper_2503_18989_amd.binding import CSegment, Config
     import ctypes
-    assert ctypes.sizeof(CSegment) == 40 and ctypes.sizeof(Config) == 52
+    assert ctypes.sizeof(CSegment) == 40 and ctypes.sizeof(Config) == 56
