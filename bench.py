@@ -296,7 +296,7 @@ def attention_legs(cfg7, dev_layers):
     fl, by = attn_work([(ln, 5) for ln in lengths], d)
     sec = prof["attn_verify"][0]
     out["verify_attn"] = dict(roof(fl, by, sec), us_per_launch=sec * 1e6, algorithmic_bytes=by,
-                              traffic=recorded_leg_traffic("attn_verify_kernel<128>"),
+                              traffic=recorded_leg_traffic("attn_verify_kernel<128, false>"),
                               traffic_source="profiles/traffic_attention_legs.txt (recorded rocprofv3 --pmc runs, not measured in this run)",
                               workload="30 devices x 5 rows, cache lengths U[1024,8192], 7B-shaped layer")
     out["verify_step_classes_us"] = {k: round(v[0] * 1e6, 2) for k, v in prof.items()}
