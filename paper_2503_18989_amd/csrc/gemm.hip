@@ -325,16 +325,14 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   X(15, 96, 256, 1, 4, 64, 3, EPI)  \
   X(16, 192, 64, 2, 2, 64, 4, EPI)  \
   X(17, 192, 256, 2, 2, 64, 2, EPI) \
-  X(18, 96, 64, 1, 2, 64, 4, EPI)   \
-  X(19, 96, 128, 1, 4, 64, 2, EPI)  \
-  X(20, 192, 128, 2, 2, 64, 2, EPI)
-constexpr int kNumTiles = 21;
+  X(18, 96, 64, 1, 2, 64, 4, EPI)
+constexpr int kNumTiles = 19;
 
 struct TileInfo { int bf, bt, waves, bkt, nstage; bool planned; };
 // `planned`: offered to the automatic choice; the others are alternative stagings of the
 // same shapes, used only when forced
 constexpr bool kPlanned[kNumTiles] = {false, true, true, true, true, true, true, true, true, true,
-                                      false, false, false, true, true, true, true, true, true, false, false};
+                                      false, false, false, true, true, true, true, true, true};
 constexpr TileInfo kTiles[kNumTiles] = {
 #define HAT_INFO(id, bf, bt, wf, wt, bkt, ns, epi) {bf, bt, (wf) * (wt), bkt, ns, kPlanned[id]},
     HAT_FOR_TILES(HAT_INFO, 0)
