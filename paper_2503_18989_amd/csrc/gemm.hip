@@ -307,7 +307,9 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
 // Heights of 96 and 192 rows exist so that the tile count can match the 256 CUs where
 // 128 / 256 leave a quarter or a third of them idle (7B-shaped QKV and gate/up at T <= 256).
 // Tile 19 is tile 1 on eight waves (two per SIMD, 64 x 128 each): measured 2-8 % faster
-// at T = 512 .. 4096 wherever the 256 x 256 shape is the right one.
+// at T = 512 .. 4096 wherever the 256 x 256 shape is the right one.  Tiles 20-22 take 224, 192
+// and 160 token rows: for batches whose row count leaves the last 256-row tile mostly empty
+// or the tile count just above a multiple of the 256 CUs (measured up to 25 % at T = 2200).
 #define HAT_FOR_TILES(X, EPI)       \
   X(0, 256, 256, 2, 2, 64, 2, EPI)  \
   X(1, 256, 256, 2, 2, 32, 4, EPI)  \
@@ -328,16 +330,27 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   X(16, 192, 64, 2, 2, 64, 4, EPI)  \
   X(17, 192, 256, 2, 2, 64, 2, EPI) \
   X(18, 96, 64, 1, 2, 64, 4, EPI)   \
-  X(19, 256, 256, 4, 2, 32, 4, EPI)
-constexpr int kNumTiles = 20;
+  X(19, 256, 256, 4, 2, 32, 4, EPI) \
+  X(20, 256, 224, 4, 1, 64, 2, EPI) \
+  X(21, 256, 192, 2, 2, 32, 4, EPI) \
+  X(22, 256, 160, 4, 1, 64, 3, EPI)
+constexpr int kNumTiles = 23;
 
-struct TileInfo { int bf, bt, waves, bkt, nstage; bool planned; };
+struct TileInfo { int bf, bt, waves, bkt, nstage; bool planned; float eff; };
 // `planned`: offered to the automatic choice; the others are alternative stagings of the
 // same shapes, used only when forced
 constexpr bool kPlanned[kNumTiles] = {false, true, true, true, true, true, true, true, true, true,
-                                      false, false, false, true, true, true, true, true, true, true};
+                                      false, false, false, true, true, true, true, true, true, true,
+                                      true, true, true};
+// Share of the matrix peak that a tile's k-loop reaches when it is not load-bound, fitted to
+// sweeps at T = 512 .. 5220 (7B shapes, all four products, K split 1 .. 8); 0 = not measured
+// there, the tile is only offered to batches of at most kSmallT rows.
+constexpr float kEff[kNumTiles] = {0.f, 0.585f, 0.538f, 0.533f, 0.916f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                                   0.f, 0.f, 0.f, 0.514f, 0.f, 1.209f, 0.f, 0.504f, 0.f, 0.629f,
+                                   0.518f, 0.565f, 0.564f};
+constexpr int kSmallT = 384;
 constexpr TileInfo kTiles[kNumTiles] = {
-#define HAT_INFO(id, bf, bt, wf, wt, bkt, ns, epi) {bf, bt, (wf) * (wt), bkt, ns, kPlanned[id]},
+#define HAT_INFO(id, bf, bt, wf, wt, bkt, ns, epi) {bf, bt, (wf) * (wt), bkt, ns, kPlanned[id], kEff[id]},
     HAT_FOR_TILES(HAT_INFO, 0)
 #undef HAT_INFO
 };
@@ -393,18 +406,25 @@ HatGemmPlan hat_gemm_plan(const HatGemm& g) {
     while (best.ksplit > 1 && ((long)best.ksplit * g.T > g.part_rows || g.K / 64 / best.ksplit < 1)) --best.ksplit;
     return best;
   }
-  // Constants fitted to tile sweeps on MI355X at T = 32 .. 3556 (7B shapes): a CU moves
-  // about 36 B/clk through direct-to-LDS loads, the MFMA loop runs at about 85 % of the
-  // matrix peak on its own, and the two overlap only partly (issuing the loads holds
-  // the waves that also issue the MFMAs).  The weight stream cannot beat ~5.5 TB/s, nor
-  // (Little's law) the bytes of W that the resident workgroups' rings keep in flight
-  // divided by the ~1.2 us a load from HBM takes under load -- which is what decides
-  // between shapes when there are few token rows.
+  // Two regimes, each with constants fitted to tile sweeps on MI355X (7B shapes).
+  // Up to kSmallT rows (T = 32 .. 384) the weight stream decides: a CU moves about 36 B/clk
+  // through direct-to-LDS loads, the MFMA loop runs at about 85 % of the matrix peak on its own,
+  // and the two overlap only partly (issuing the loads holds the waves that also issue the
+  // MFMAs); the weight stream cannot beat ~5.5 TB/s, nor (Little's law) the bytes of W that
+  // the resident workgroups' rings keep in flight divided by the ~1.2 us a load from HBM takes
+  // under load -- which is what decides between shapes when there are few token rows.
+  // Above that (T = 512 .. 5220) a k-tile costs the larger of its MFMA time at the tile's own
+  // measured efficiency and its load time at 28 B/clk, a round of workgroups costs ~3.7 us of
+  // prologue and drain, and the epilogue's traffic is not hidden: 14 B/clk per CU for the
+  // fp16 stores, 6.2 for the read-modify-write of the fp32 residual, 7.2 for split-K partial
+  // sums (written here, read back by the consumer of the residual).
   double best_cost = 1e300;
   const int KT = g.K / 64;
+  const bool large = g.T > kSmallT;
   for (int c = 0; c < kNumTiles; ++c) {
     const TileInfo& q = kTiles[c];
     if (!q.planned) continue;
+    if (large ? q.eff == 0.f : (q.bt & (q.bt - 1)) != 0) continue;   // 160/192/224-row token tiles: large batches only
     const int nT = (g.T + q.bt - 1) / q.bt, nF = (g.Nw + q.bf - 1) / q.bf;
     const int max_split = (g.epilogue == HAT_EPI_RESID && g.part) ? 16 : 1;
     const int lds = q.nstage * (q.bf + q.bt) * q.bkt * 2;
@@ -414,12 +434,24 @@ HatGemmPlan hat_gemm_plan(const HatGemm& g) {
       const double blocks = (double)nT * nF * ks;
       const double rounds = std::ceil(blocks / 256.0);
       const double kt = std::ceil((double)KT / ks) + 2.0;                     // + pipeline fill
-      const double mfma_eff = q.waves == 8 ? 0.90 : 0.85;                     // two waves per SIMD fill more of the pipe
-      const double mfma_cyc = 2.0 * q.bf * q.bt * 64 / (4 * 1017.0 * mfma_eff);  // per k-tile, 4 SIMDs
-      const double load_cyc = (q.bf + q.bt) * 64 * 2 / 36.0;                  // per k-tile
-      const double tile_cyc = std::max(mfma_cyc, load_cyc) + 0.45 * std::min(mfma_cyc, load_cyc);
-      double cyc = rounds * kt * tile_cyc + rounds * 3000.0;
-      if (ks > 1) cyc += (double)ks * g.T * g.Nout * 8.0 / 256.0 / 12.0;      // partial write + read, per CU
+      double cyc;
+      if (large) {
+        const double mfma_cyc = 2.0 * q.bf * q.bt * 64 / (4 * 1017.0 * q.eff);  // per k-tile, 4 SIMDs
+        const double load_cyc = (q.bf + q.bt) * 64 * 2 / 28.1;
+        const double tile_cyc = std::max(mfma_cyc, load_cyc) + 0.073 * std::min(mfma_cyc, load_cyc);
+        cyc = rounds * kt * tile_cyc + rounds * 8938.0;
+        const double rows = (double)g.T * g.Nout / 256.0;                     // output elements per CU
+        if (g.epilogue != HAT_EPI_RESID) cyc += rows * 2.0 / 14.0;
+        else if (ks == 1) cyc += rows * 8.0 / 6.2;
+        else cyc += rows * 8.0 * ks / 7.15;
+      } else {
+        const double mfma_eff = q.waves == 8 ? 0.90 : 0.85;                     // two waves per SIMD fill more of the pipe
+        const double mfma_cyc = 2.0 * q.bf * q.bt * 64 / (4 * 1017.0 * mfma_eff);
+        const double load_cyc = (q.bf + q.bt) * 64 * 2 / 36.0;
+        const double tile_cyc = std::max(mfma_cyc, load_cyc) + 0.45 * std::min(mfma_cyc, load_cyc);
+        cyc = rounds * kt * tile_cyc + rounds * 3000.0;
+        if (ks > 1) cyc += (double)ks * g.T * g.Nout * 8.0 / 256.0 / 12.0;    // partial write + read, per CU
+      }
       const double resident = std::min(blocks, 256.0 * per_cu);
       const double inflight = resident * q.bf * q.bkt * 2.0 * (q.nstage - 1);
       const double bw = std::min(5.5e12, inflight / 1.2e-6);
