@@ -475,6 +475,47 @@ def chunk_size_rule(points, d):
     return out
 
 
+# ---------------------------------------------------------------- GEMM classes beside the vendor BLAS (context)
+def gemm_reference(rows=(150, 256, 1024, 3556, 4096), model="7b"):
+    """The four GEMM classes of one layer as this library runs them (event-bracketed, inside a 2-layer
+    model; QKV, gate/up with SwiGLU applied, O and down with the fp32 residual update) beside a plain
+    `x @ w.T` of the same shapes through the vendor BLAS that PyTorch-ROCm links (fp16 in, fp16 out, no
+    epilogue).  A reference point for reading the MFMA fractions: nothing in the product path calls it."""
+    import torch
+    from paper_2503_18989_amd import HatMid, Segment
+    base = hi.MID13B if model == "13b" else hi.MID7B
+    cfg = hi.with_layers(base, 2)
+    d, F = cfg["d_model"], cfg["d_ffn"]
+    dev = upload(gen_weights(cfg, SEED, 2))
+    out = {"model": model, "rows": {}}
+    for T in rows:
+        m = HatMid(cfg, dev, n_pages=2 * T // 16 + 8, max_devices=2, max_step_tokens=max(T, 256), max_pos=2 * T)
+        x = to_dev_bf16(hi.hidden_rows(T, d, SEED, 0))
+
+        def run(n):
+            for _ in range(n):
+                m.release(0)
+                m.forward([Segment(0, hi.CHUNK, 0, x)])
+        run(3)
+        prof = profile_classes(m, lambda: run(10))
+        row = {}
+        for name, N, K in (("gemm_qkv", 3 * d, d), ("gemm_o", d, d), ("gemm_gateup", 2 * F, d), ("gemm_down", d, F)):
+            a16 = torch.randn(T, K, device="cuda", dtype=torch.float16)
+            w16 = torch.randn(N, K, device="cuda", dtype=torch.float16)
+            for _ in range(3):
+                a16 @ w16.t()
+            ms = timed_steps(lambda: a16 @ w16.t(), 20)
+            fl = 2.0 * T * N * K
+            ours = prof[name][0]
+            row[name] = {"us": round(ours * 1e6, 1), "mfma_frac": round(fl / ours / PEAK_MFMA_BF16, 3),
+                         "vendor_us": round(ms * 1e3, 1), "vendor_mfma_frac": round(fl / (ms * 1e-3) / PEAK_MFMA_BF16, 3)}
+            del a16, w16
+        out["rows"][str(T)] = row
+        log("gemm reference, %s, T=%d: %s" % (model, T, row))
+        m.close()
+    return out
+
+
 # ---------------------------------------------------------------- measured peaks (microbenchmarks in the library)
 def measured_peaks():
     """hat_mid_debug_peak: what the chip delivers through the instruction mixes of this library's kernels."""
@@ -557,6 +598,8 @@ def main():
     ap.add_argument("--sweep-layers", type=int, default=38, help="depth of the chunk-size sweep model")
     ap.add_argument("--host-fed-only", action="store_true", help="only the headline workload, device-fed and host-fed, and the uplink emulation")
     ap.add_argument("--peaks", action="store_true", help="only the machine microbenchmarks (hat_mid_debug_peak): prints them as JSON and exits")
+    ap.add_argument("--gemm-reference", action="store_true",
+                    help="only the GEMM classes beside the vendor BLAS on the same shapes (7B and 13B shapes): prints JSON and exits")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling FETCH_SIZE/WRITE_SIZE counters)")
     a = ap.parse_args()
@@ -569,6 +612,9 @@ def main():
     from paper_2503_18989_amd import HatMid
     if a.peaks:
         print(json.dumps({"measured_peaks": measured_peaks()}))
+        return
+    if a.gemm_reference:
+        print(json.dumps({"gemm_reference": [gemm_reference(model="7b"), gemm_reference(rows=(1024, 4096, 8192), model="13b")]}))
         return
     cfg = dict(hi.MID7B)
     if a.layers:
