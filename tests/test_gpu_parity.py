@@ -413,6 +413,24 @@ def test_widths_that_are_not_multiples_of_the_tiles(cfg):
     p.close()
 
 
+@pytest.mark.parametrize("cfg", [
+    SMALL64,
+    dict(name="odd128", n_layers=2, d_model=384, n_heads=3, head_dim=128, d_ffn=1000, rms_eps=1e-6, rope_theta=5e5),
+    dict(name="wide128", n_layers=1, d_model=4224, n_heads=33, head_dim=128, d_ffn=512, rms_eps=1e-5, rope_theta=1e4),
+], ids=["d256", "d384", "d4224"])
+def test_a_thousand_rows_and_more_in_one_step(cfg):
+    # from 1024 rows on RMSNorm works on groups of 4 rows (two instantiations: rows of up to 4096 and of up to
+    # 8192 floats): 1030 and 1027 rows leave a ragged last group; the second pass splits K of the O and down
+    # projections, so the norm also folds their partial sums in
+    p = Pair(cfg, 83, n_pages=140, max_devices=3, max_step_tokens=1100, max_pos=1100)
+    check(*p.step([(0, hi.CHUNK, 0, 1030)]))
+    for which in (1, 3):
+        p.gpu.force_gemm(which, 4, 2)
+    check(*p.step([(1, hi.CHUNK, 0, 1027), (2, hi.CHUNK, 0, 3)]))
+    p.check_pages([0, 1, 2])
+    p.close()
+
+
 @KV
 def test_positions_beyond_twenty_thousand(kv):
     # a 20 000-row cache installed by import, then a 200-row chunk, a chain and a tree at positions
