@@ -560,7 +560,7 @@ def recorded_leg_traffic(kernel):
     try:
         for line in open(path):
             if line.startswith(kernel):
-                f = dict(kv.split("=") for kv in line.split()[1:])
+                f = dict(kv.split("=") for kv in line[len(kernel):].split())   # (the kernel name itself contains a space)
                 return float(f["fetch_bytes"]) + float(f["write_bytes"])
     except OSError:
         pass
