@@ -279,11 +279,13 @@ __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const 
   const int octs = hd >> 3;
   const int vidx = idx - n_a;
   if (vidx >= p.n_append * H * 2 * octs) return;
-  const HatAppendItem it = p.append[vidx % p.n_append];   // consecutive lanes: consecutive pages
-  const int vrem = vidx / p.n_append;
-  const int o = vrem % octs;
-  const int half = (vrem / octs) & 1;
-  const int hh = vrem / (2 * octs);
+  // consecutive lanes: the octets and the two slot halves of one (page, head), so that one wave
+  // writes whole V tiles (4 KB each at hd = 128) and reads whole 256-byte runs of the rows
+  const int o = vidx % octs;
+  const int half = (vidx / octs) & 1;
+  const int vrem = vidx / (2 * octs);
+  const HatAppendItem it = p.append[vrem % p.n_append];
+  const int hh = vrem / p.n_append;
   kv_t* vt = pool + ((size_t)hh * n_pages + it.page) * kv_head_elems(hd) + 16 * hd;
   f16x8 rows[8];
   bool valid[8];
