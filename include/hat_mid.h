@@ -370,6 +370,12 @@ hat_status_t hat_mid_debug_peak(int32_t kind, void* buf, size_t bytes, int32_t i
  * hat_mid_debug_force_gemm are 0 .. count-1).  No GPU work. */
 int32_t hat_mid_debug_gemm_tile_count(void);
 
+/* Shape of entry `tile` of that table: output features x token rows of one workgroup tile, its
+ * waves, the k extent of one ring stage and the number of stages (host pointers; any may be null).
+ * HAT_EINVAL if `tile` is out of range.  No GPU work; for tests of the planner. */
+hat_status_t hat_mid_debug_gemm_tile_info(int32_t tile, int32_t* features, int32_t* tokens, int32_t* waves,
+                                          int32_t* k_per_stage, int32_t* stages);
+
 #ifdef __cplusplus
 }
 #endif

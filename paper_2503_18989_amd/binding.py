@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "hat_mid_destroy", "hat_mid_last_error", "hat_mid_kv_query", "hat_mid_kv_compact", "hat_mid_kv_import", "hat_mid_kv_export",
     "hat_mid_kv_export_static",
     "hat_mid_last_step_stats", "hat_mid_set_profiling", "hat_mid_kernel_times", "hat_mid_debug_dump", "hat_mid_debug_force_gemm",
-    "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_plan", "hat_mid_debug_create_host_only", "hat_mid_debug_plan",
+    "hat_mid_debug_gemm_tile_count", "hat_mid_debug_gemm_tile_info", "hat_mid_debug_gemm_plan", "hat_mid_debug_create_host_only", "hat_mid_debug_plan",
     "hat_mid_debug_set_attn_targets", "hat_mid_debug_limit_plan", "hat_mid_debug_set_verify_probe", "hat_mid_debug_peak",
     "hat_sched_create", "hat_sched_destroy", "hat_sched_observe", "hat_sched_mu", "hat_sched_predict",
     "hat_sched_chunk_size", "hat_sched_parallel_draft_steps",
@@ -111,6 +111,8 @@ def load_library():
     lib.hat_mid_debug_force_gemm.argtypes = [vp, i32, i32, i32]
     lib.hat_mid_debug_gemm_tile_count.restype = i32
     lib.hat_mid_debug_gemm_tile_count.argtypes = []
+    lib.hat_mid_debug_gemm_tile_info.restype = i32
+    lib.hat_mid_debug_gemm_tile_info.argtypes = [i32] + [C.POINTER(i32)] * 5
     lib.hat_mid_debug_gemm_plan.restype = i32
     lib.hat_mid_debug_gemm_plan.argtypes = [i32, i32, i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.hat_mid_debug_create_host_only.restype = i32

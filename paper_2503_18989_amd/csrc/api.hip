@@ -1160,6 +1160,18 @@ hat_status_t hat_mid_debug_force_gemm(hat_mid_t* h, int32_t which, int32_t tile,
 
 int32_t hat_mid_debug_gemm_tile_count(void) { return hat_gemm_tile_count(); }
 
+hat_status_t hat_mid_debug_gemm_tile_info(int32_t tile, int32_t* features, int32_t* tokens, int32_t* waves,
+                                          int32_t* k_per_stage, int32_t* stages) {
+  int bf, bt, w, bk, ns;
+  if (!hat_gemm_tile_info(tile, &bf, &bt, &w, &bk, &ns)) return HAT_EINVAL;
+  if (features) *features = bf;
+  if (tokens) *tokens = bt;
+  if (waves) *waves = w;
+  if (k_per_stage) *k_per_stage = bk;
+  if (stages) *stages = ns;
+  return HAT_OK;
+}
+
 hat_status_t hat_mid_debug_set_attn_targets(hat_mid_t* h, int32_t chunk_target, int32_t verify_target) {
   if (!h || chunk_target < 0 || verify_target < 0) return HAT_EINVAL;
   if (chunk_target > 0) h->s.attn_target = chunk_target;

@@ -385,6 +385,16 @@ hipError_t attr_epi() {
 }  // namespace
 
 int hat_gemm_tile_count() { return kNumTiles; }
+bool hat_gemm_tile_info(int id, int* bf, int* bt, int* waves, int* bkt, int* nstage) {
+  if (id < 0 || id >= kNumTiles) return false;
+  const TileInfo& q = kTiles[id];
+  if (bf) *bf = q.bf;
+  if (bt) *bt = q.bt;
+  if (waves) *waves = q.waves;
+  if (bkt) *bkt = q.bkt;
+  if (nstage) *nstage = q.nstage;
+  return true;
+}
 
 hipError_t hat_gemm_init() {
   hipError_t e;

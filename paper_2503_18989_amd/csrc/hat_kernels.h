@@ -43,6 +43,8 @@ struct HatGemmPlan {
 HatGemmPlan hat_gemm_plan(const HatGemm& g);
 hipError_t hat_launch_gemm(const HatGemm& g, const HatGemmPlan& p, hipStream_t st);
 int hat_gemm_tile_count();
+// shape of tile `id` (features, tokens, waves, k per stage, stages); false if out of range
+bool hat_gemm_tile_info(int id, int* bf, int* bt, int* waves, int* bkt, int* nstage);
 hipError_t hat_gemm_init();  // one-time function attributes (dynamic LDS size)
 
 // ---- weight re-tiling (create time) -----------------------------------------

@@ -13,6 +13,7 @@
 HatGemmPlan hat_gemm_plan(const HatGemm&) { return HatGemmPlan{0, 1}; }
 hipError_t hat_launch_gemm(const HatGemm&, const HatGemmPlan&, hipStream_t) { return hipErrorUnknown; }
 int hat_gemm_tile_count() { return 0; }
+bool hat_gemm_tile_info(int, int*, int*, int*, int*, int*) { return false; }
 hipError_t hat_gemm_init() { return hipErrorUnknown; }
 hipError_t hat_launch_retile(act_t*, int, int, const bf16_t*, const bf16_t*, const bf16_t*, int, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t hat_launch_bf16_to_f32(const bf16_t*, float*, int, hipStream_t) { return hipErrorUnknown; }

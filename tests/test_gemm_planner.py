@@ -53,3 +53,44 @@ def test_small_batches_split_k_and_large_ones_do_not(lib):
 
 def test_null_outputs_are_refused(lib):
     assert lib.hat_mid_debug_gemm_plan(256, 4096, 4096, 4096, 2, 4096, None, None) == -1
+
+
+def tile_info(lib, tile):
+    v = [C.c_int32(-1) for _ in range(5)]
+    rc = lib.hat_mid_debug_gemm_tile_info(tile, *[C.byref(x) for x in v])
+    return rc, tuple(x.value for x in v)
+
+
+def test_tile_table_fits_the_hardware(lib):
+    n = lib.hat_mid_debug_gemm_tile_count()
+    assert n >= 20
+    for t in range(n):
+        rc, (bf, bt, waves, bk, ns) = tile_info(lib, t)
+        assert rc == 0
+        assert bf % 32 == 0 and bt % 32 == 0 and bk % 16 == 0 and 2 <= ns <= 4
+        assert waves in (2, 4, 8)
+        assert ns * (bf + bt) * bk * 2 <= 160 * 1024, "ring of tile %d exceeds the LDS of a CU" % t
+        # accumulators (fp32, 64 lanes per wave) + operands must fit the register file of the waves' SIMDs
+        acc_regs = bf * bt // (waves * 64)
+        assert acc_regs <= (256 if waves == 8 else 512) - 56, "tile %d: %d accumulator registers per lane" % (t, acc_regs)
+    assert tile_info(lib, n)[0] == -1 and tile_info(lib, -1)[0] == -1
+    assert lib.hat_mid_debug_gemm_tile_info(0, None, None, None, None, None) == 0
+
+
+def test_small_batches_keep_power_of_two_token_tiles_and_large_ones_use_the_big_tile(lib):
+    for T in (1, 32, 150, 256, 384):
+        for name, (Nw, Nout, K, epi) in SHAPES.items():
+            tile, _ = plan(lib, T, Nw, Nout, K, epi, 4096)
+            bt = tile_info(lib, tile)[1][1]
+            assert bt & (bt - 1) == 0, "%s at T=%d took a %d-row token tile" % (name, T, bt)
+    for name in ("qkv7", "gu7", "qkv13", "gu13"):
+        Nw, Nout, K, epi = SHAPES[name]
+        tile, ks = plan(lib, 8192, Nw, Nout, K, epi, 4096)
+        bf, bt, waves = tile_info(lib, tile)[1][:3]
+        assert (bf, bt, waves, ks) == (256, 256, 8, 1), name
+    # 2200 rows: 8.6 tiles of 256 rows; the 160-row tile (13.75 -> 14 tiles, 2 % padding instead of 5 %, and a tile count
+    # that packs the 256 CUs better) measured 21-23 % faster on the O and down projections
+    for name in ("o7", "down7"):
+        Nw, Nout, K, epi = SHAPES[name]
+        tile, ks = plan(lib, 2200, Nw, Nout, K, epi, 4096)
+        assert tile_info(lib, tile)[1][1] in (160, 192)
