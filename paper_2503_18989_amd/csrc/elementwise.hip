@@ -226,23 +226,29 @@ __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(float* __restrict__ r
 }
 
 // ---------------------------------------------------------------- RoPE + KV append
-// Two kinds of threads in one launch.
-//  (a) one per (row, head, octet pair): octets o and o + hd/16 hold the two halves of 8
-//      rotation pairs.  q is rotated in place (fp16); rotated k is rounded to bf16 and
-//      written to the row's (page, slot) of this layer's pool as two 16-byte octets.
-//  (b) one per (appended page, head, slot half, octet of v): gathers the octet of the 8
-//      rows whose slots share a lane half, transposes in registers and writes, per
-//      feature, the 8 slots as one 16-byte run of the V tile (whose order is
-//      [feature][slot]); slots that are not new in this step keep their old contents.
-template <bool KVF16>
-__global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const float2* __restrict__ table,
-                                   kv_t* __restrict__ pool, int n_pages, int H, int hd) {
-  const int half_oct = hd >> 4;                 // octets per half head
-  const int per_row = H * half_oct;
-  const int n_a = p.T * per_row;
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+// Two kinds of workgroups in one launch.
+//  (a) the first n_kblocks: one thread per (row, head, octet pair): octets o and o + hd/16 hold
+//      the two halves of 8 rotation pairs.  q is rotated in place (fp16); rotated k is rounded
+//      to the cache type and written to the row's (page, slot) of this layer's pool as two
+//      16-byte octets.
+//  (b) the rest: one workgroup per V tile of an appended (page, head) (two tiles at hd = 64).
+//      A thread loads one 16-byte octet of one of the page's 16 rows (consecutive lanes:
+//      consecutive rows, 256-byte runs of the P32 layout), scatters its 8 values into an LDS
+//      image of the tile (whose order is [hd/32][slot half][feature][8 slots]), and after the
+//      barrier writes one 16-byte piece of the image: the workgroup stores the tile as one
+//      contiguous run.  Slots that are not new in this step keep their old contents.
+template <bool KVF16, int HD>
+__global__ __launch_bounds__(256) void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv,
+                                                           const float2* __restrict__ table, kv_t* __restrict__ pool,
+                                                           int n_pages, int H, int n_kblocks) {
+  constexpr int hd = HD;
+  constexpr int half_oct = hd >> 4;             // octets per half head
   const int d = H * hd, row_len = 3 * d;
-  if (idx < n_a) {
+  if ((int)blockIdx.x < n_kblocks) {
+    const int per_row = H * half_oct;
+    const int n_a = p.T * per_row;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n_a) return;
     // consecutive lanes take consecutive rows of one (head, octet pair): 32 rows of a
     // P32 panel are one 512-byte run, and consecutive slots of a K tile are contiguous
     const int t = idx % p.T, rem = idx / p.T;
@@ -276,41 +282,47 @@ __global__ void rope_append_kernel(HatPlanDev p, act_t* __restrict__ qkv, const 
     *(kvx8*)(kt + ktile_index(slot, o * 8 + (hd >> 1))) = to_kv<KVF16>(rkh);
     return;
   }
-  const int octs = hd >> 3;
-  const int vidx = idx - n_a;
-  if (vidx >= p.n_append * H * 2 * octs) return;
-  // consecutive lanes: the octets and the two slot halves of one (page, head), so that one wave
-  // writes whole V tiles (4 KB each at hd = 128) and reads whole 256-byte runs of the rows
-  const int o = vidx % octs;
-  const int half = (vidx / octs) & 1;
-  const int vrem = vidx / (2 * octs);
-  const HatAppendItem it = p.append[vrem % p.n_append];
-  const int hh = vrem / p.n_append;
-  kv_t* vt = pool + ((size_t)hh * n_pages + it.page) * kv_head_elems(hd) + 16 * hd;
-  f16x8 rows[8];
-  bool valid[8];
-  bool all = true;
+  constexpr int PIECES = hd * 2;       // 16-byte pieces of one V tile (16 slots x hd two-byte elements)
+  constexpr int TPB = 256 / PIECES;    // tiles per workgroup
+  // 16 bytes of padding after every 512 (one slot half of a 32-feature block), so that the two
+  // slot halves and neighbouring octets do not fall on the same banks when the rows are scattered
+  constexpr int IMG = PIECES * 16 + (PIECES / 32) * 16;
+  __shared__ __attribute__((aligned(16))) unsigned char image[TPB][IMG];
+  const int tb = threadIdx.x / PIECES, q = threadIdx.x % PIECES;
+  const int tix = ((int)blockIdx.x - n_kblocks) * TPB + tb;
+  const bool live = tix < p.n_append * H;
+  HatAppendItem it{};
+  int hh = 0;
+  if (live) {
+    it = p.append[tix % p.n_append];
+    hh = tix / p.n_append;
+    const int r = q & 15, o = q >> 4;   // slot and octet of this thread's load
+    const int pos = it.pos0 + r;
+    if (pos >= it.lo && pos < it.hi) {
+      const f16x8 x = *(const f16x8*)(qkv + p32_index(it.row0 + r, 2 * d + hh * hd + o * 8, row_len));
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int slot = 8 * (j >> 2) + 4 * half + (j & 3);
-    const int pos = it.pos0 + slot;
-    valid[j] = pos >= it.lo && pos < it.hi;
-    all = all && valid[j];
-    if (valid[j]) rows[j] = *(const f16x8*)(qkv + p32_index(it.row0 + slot, 2 * d + hh * hd + o * 8, row_len));
-  }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    kv_t* dst = vt + vtile_index(4 * half, o * 8 + e);   // j = 0 of this half: 8 slots follow contiguously
-    kvx8 out;
-    if (!all) out = *(const kvx8*)dst;
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (valid[j]) {
-        const _Float16 x = rows[j][e];   // (a copy: bit_cast must not be handed the vector element itself)
-        out[j] = KVF16 ? __builtin_bit_cast(kv_t, x) : float_to_kv<false>((float)x);
+      for (int e = 0; e < 8; ++e) {
+        int byte = vtile_index(r, o * 8 + e) * 2;
+        byte += (byte >> 9) * 16;
+        const _Float16 xe = x[e];   // (a copy: bit_cast must not be handed the vector element itself)
+        *(kv_t*)(&image[tb][byte]) = KVF16 ? __builtin_bit_cast(kv_t, xe) : float_to_kv<false>((float)xe);
       }
-    *(kvx8*)dst = out;
+    }
   }
+  __syncthreads();
+  if (!live) return;
+  kv_t* dst = pool + ((size_t)hh * n_pages + it.page) * kv_head_elems(hd) + 16 * hd + q * 8;
+  kvx8 out = *(const kvx8*)(&image[tb][q * 16 + (q >> 5) * 16]);
+  if (it.lo > it.pos0 || it.hi < it.pos0 + 16) {   // a partly new page: the other slots keep what they hold
+    const kvx8 old = *(const kvx8*)dst;
+    const int h = (q >> 5) & 1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int pos = it.pos0 + 8 * (j >> 2) + 4 * h + (j & 3);
+      if (pos < it.lo || pos >= it.hi) out[j] = old[j];
+    }
+  }
+  *(kvx8*)dst = out;
 }
 
 // ---------------------------------------------------------------- weight re-tiling
@@ -479,9 +491,19 @@ hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const
 }
 hipError_t hat_launch_rope_append(const HatPlanDev& p, act_t* qkv, const float2* table, kv_t* pool_layer,
                                   int n_pages, int H, int hd, int kv_f16, hipStream_t st) {
-  const size_t n = (size_t)p.T * H * (hd >> 4) + (size_t)p.n_append * H * 2 * (hd >> 3);
-  if (kv_f16) rope_append_kernel<true><<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, hd);
-  else rope_append_kernel<false><<<blocks_for(n, 256), 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, hd);
+  const int n_kblocks = (int)(((size_t)p.T * H * (hd >> 4) + 255) / 256);
+  const int tiles = p.n_append * H;
+  if (hd == 128) {
+    const dim3 grid(n_kblocks + tiles);
+    if (kv_f16) rope_append_kernel<true, 128><<<grid, 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, n_kblocks);
+    else rope_append_kernel<false, 128><<<grid, 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, n_kblocks);
+  } else if (hd == 64) {
+    const dim3 grid(n_kblocks + (tiles + 1) / 2);
+    if (kv_f16) rope_append_kernel<true, 64><<<grid, 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, n_kblocks);
+    else rope_append_kernel<false, 64><<<grid, 256, 0, st>>>(p, qkv, table, pool_layer, n_pages, H, n_kblocks);
+  } else {
+    return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 hipError_t hat_launch_retile(act_t* dst, int Nw, int Kd, const bf16_t* src0, const bf16_t* src1, const bf16_t* src2,
