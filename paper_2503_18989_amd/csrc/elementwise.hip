@@ -482,7 +482,8 @@ hipError_t hat_launch_rope_table(const HatPlanDev& p, const double* inv_freq, fl
 hipError_t hat_launch_rmsnorm(float* resid, const float* part, int nparts, const float* gain, act_t* outP, int T,
                               int d, float eps, hipStream_t st) {
   if (d > 8192 || (d & 7)) return hipErrorInvalidValue;
-  // from about a thousand rows on there are enough groups of rows to fill the chip
+  // from about a thousand rows on there are enough groups of rows to fill the chip (at 150-768 rows the
+  // one-row kernel measured 10-14 us against 15-20 us)
   const bool groups = T >= 1024 && d % 64 == 0;   // (d / 8 a multiple of 8: the chunk swizzle stays inside the row)
   if (groups && d <= 4096) rmsnorm_rows_kernel<4, 4096><<<(T + 3) / 4, 256, 0, st>>>(resid, part, nparts, T, gain, outP, d, eps);
   else if (groups) rmsnorm_rows_kernel<4, 8192><<<(T + 3) / 4, 256, 0, st>>>(resid, part, nparts, T, gain, outP, d, eps);
