@@ -109,6 +109,28 @@ __global__ void rope_table_kernel(HatPlanDev p, const double* __restrict__ inv_f
   table[idx] = make_float2((float)c, (float)s);
 }
 
+// a, b += the 8 floats at pp of each of the nparts split-K partial sums (pstride floats apart), added in
+// ascending order of the split.  The loads of four splits are issued before the first of them is
+// used: a loop that loads one split per pass waits out a memory round trip per split.
+__device__ __forceinline__ void fold_partials(f32x4& a, f32x4& b, const float* __restrict__ pp, size_t pstride, int nparts) {
+  for (int q0 = 0; q0 < nparts; q0 += 4) {
+    f32x4 pa[4], pb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (q0 + u < nparts) {
+        const float* src = pp + (size_t)(q0 + u) * pstride;
+        pa[u] = *(const f32x4*)src;
+        pb[u] = *(const f32x4*)(src + 4);
+      }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (q0 + u < nparts) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { a[e] += pa[u][e]; b[e] += pb[u][e]; }
+      }
+  }
+}
+
 // ---------------------------------------------------------------- RMSNorm
 // one workgroup (256 threads) per row: x = resid + pending split-K partial sums
 // (written back), y = x * rsqrt(mean(x^2) + eps) * gain as fp16 in P32 layout.
@@ -127,12 +149,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ resid,
     const int i = (v * 256 + threadIdx.x) * 8;
     if (i < d) {
       f32x4 a = *(const f32x4*)(x + i), b = *(const f32x4*)(x + i + 4);
-      for (int q = 0; q < nparts; ++q) {
-        const float* pp = part + q * pstride + (size_t)t * d + i;
-        const f32x4 pa = *(const f32x4*)pp, pb = *(const f32x4*)(pp + 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { a[e] += pa[e]; b[e] += pb[e]; }
-      }
+      fold_partials(a, b, part + (size_t)t * d + i, pstride, nparts);
       if (nparts > 0) { *(f32x4*)(x + i) = a; *(f32x4*)(x + i + 4) = b; }
 #pragma unroll
       for (int e = 0; e < 4; ++e) ss += a[e] * a[e] + b[e] * b[e];
@@ -189,12 +206,7 @@ __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(float* __restrict__ r
       const int i = (v * 64 + lane) * 8;
       if (i < d) {
         f32x4 a = *(const f32x4*)(x + i), b = *(const f32x4*)(x + i + 4);
-        for (int q = 0; q < nparts; ++q) {
-          const float* pp = part + q * pstride + (size_t)t * d + i;
-          const f32x4 pa = *(const f32x4*)pp, pb = *(const f32x4*)(pp + 4);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { a[e] += pa[e]; b[e] += pb[e]; }
-        }
+        fold_partials(a, b, part + (size_t)t * d + i, pstride, nparts);
         if (nparts > 0) { *(f32x4*)(x + i) = a; *(f32x4*)(x + i + 4) = b; }
 #pragma unroll
         for (int e = 0; e < 4; ++e) ss += a[e] * a[e] + b[e] * b[e];
