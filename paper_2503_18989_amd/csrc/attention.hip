@@ -709,19 +709,39 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(HatAttn a, const HatMer
   const int head = blockIdx.y;
   for (int idx = threadIdx.x; idx < it.nrows * (HD / 8); idx += 256) {
     const int r = idx / (HD / 8), e = (idx % (HD / 8)) * 8;
+    // both passes take the key ranges four at a time, loads first: a loop that loads one range per
+    // pass waits out a memory round trip per range (the order of the sums is unchanged)
+    const size_t pr0 = (size_t)(it.part_row + r) * a.H + head, prs = (size_t)it.stride * a.H;
     float M = -INFINITY;
-    for (int s = 0; s < it.nsplit; ++s)
-      M = fmaxf(M, a.part_ml[(size_t)(it.part_row + s * it.stride + r) * a.H + head].x);
+    for (int s0 = 0; s0 < it.nsplit; s0 += 4) {
+      float mx[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (s0 + u < it.nsplit) mx[u] = a.part_ml[pr0 + (s0 + u) * prs].x;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (s0 + u < it.nsplit) M = fmaxf(M, mx[u]);
+    }
     float L = 0.f;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int s = 0; s < it.nsplit; ++s) {
-      const size_t pr = (size_t)(it.part_row + s * it.stride + r) * a.H + head;
-      const float2 ml = a.part_ml[pr];
-      const float f = ml.y * exp2f(ml.x - M);   // weight of this key range: its sum, on the common scale
-      L += f;
-      const f16x8 v = *(const f16x8*)(a.part_o + pr * HD + e);
+    for (int s0 = 0; s0 < it.nsplit; s0 += 4) {
+      float2 ml[4];
+      f16x8 v[4];
 #pragma unroll
-      for (int x = 0; x < 8; ++x) acc[x] += (float)v[x] * f;
+      for (int u = 0; u < 4; ++u)
+        if (s0 + u < it.nsplit) {
+          const size_t pr = pr0 + (s0 + u) * prs;
+          ml[u] = a.part_ml[pr];
+          v[u] = *(const f16x8*)(a.part_o + pr * HD + e);
+        }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (s0 + u < it.nsplit) {
+          const float f = ml[u].y * exp2f(ml[u].x - M);   // weight of this key range: its sum, on the common scale
+          L += f;
+#pragma unroll
+          for (int x = 0; x < 8; ++x) acc[x] += (float)v[u][x] * f;
+        }
     }
     const float inv = 1.0f / L;
     f16x8 ov;
