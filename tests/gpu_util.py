@@ -35,7 +35,8 @@ def tol_for_depth(n_layers):
 
 
 def progress(msg):
-    """One line to gpurun_out/test_progress.log (pytest captures stdout; long tests report here)."""
+    """One line to test_progress.log in the output folder of a GPU run (pytest captures stdout; long tests
+    report their figures and their progress here)."""
     import os
     import time
     d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
