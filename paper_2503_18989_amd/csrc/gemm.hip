@@ -309,7 +309,10 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
 // Tile 19 is tile 1 on eight waves (two per SIMD, 64 x 128 each): measured 2-8 % faster
 // at T = 512 .. 4096 wherever the 256 x 256 shape is the right one.  Tiles 20-22 take 224, 192
 // and 160 token rows: for batches whose row count leaves the last 256-row tile mostly empty
-// or the tile count just above a multiple of the 256 CUs (measured up to 25 % at T = 2200).
+// or the tile count just above a multiple of the 256 CUs (measured up to 25 % at T = 2200).  Tile 23
+// (128 x 160) is for batches of 129 .. 160 rows, e.g. 30 devices x 5 draft rows: one token tile
+// instead of a full and a nearly empty one (O, gate/up and down 3-13 % faster at 150 rows on the
+// 7B shape, 12-20 % on the 13B shape).
 #define HAT_FOR_TILES(X, EPI)       \
   X(0, 256, 256, 2, 2, 64, 2, EPI)  \
   X(1, 256, 256, 2, 2, 32, 4, EPI)  \
@@ -333,21 +336,22 @@ __global__ __launch_bounds__(WF* WT * 64) void gemm_kernel(HatGemm g, int ksplit
   X(19, 256, 256, 4, 2, 32, 4, EPI) \
   X(20, 256, 224, 4, 1, 64, 2, EPI) \
   X(21, 256, 192, 2, 2, 32, 4, EPI) \
-  X(22, 256, 160, 4, 1, 64, 3, EPI)
-constexpr int kNumTiles = 23;
+  X(22, 256, 160, 4, 1, 64, 3, EPI) \
+  X(23, 128, 160, 4, 1, 64, 3, EPI)
+constexpr int kNumTiles = 24;
 
 struct TileInfo { int bf, bt, waves, bkt, nstage; bool planned; float eff; };
 // `planned`: offered to the automatic choice; the others are alternative stagings of the
 // same shapes, used only when forced
 constexpr bool kPlanned[kNumTiles] = {false, true, true, true, true, true, true, true, true, true,
                                       false, false, false, true, true, true, true, true, true, true,
-                                      true, true, true};
+                                      true, true, true, true};
 // Share of the matrix peak that a tile's k-loop reaches when it is not load-bound, fitted to
 // sweeps at T = 512 .. 5220 (7B shapes, all four products, K split 1 .. 8); 0 = not measured
 // there, the tile is only offered to batches of at most kSmallT rows.
 constexpr float kEff[kNumTiles] = {0.f, 0.585f, 0.538f, 0.533f, 0.916f, 0.f, 0.f, 0.f, 0.f, 0.f,
                                    0.f, 0.f, 0.f, 0.514f, 0.f, 1.209f, 0.f, 0.504f, 0.f, 0.629f,
-                                   0.518f, 0.565f, 0.564f};
+                                   0.518f, 0.565f, 0.564f, 0.f};
 constexpr int kSmallT = 384;
 constexpr TileInfo kTiles[kNumTiles] = {
 #define HAT_INFO(id, bf, bt, wf, wt, bkt, ns, epi) {bf, bt, (wf) * (wt), bkt, ns, kPlanned[id], kEff[id]},
@@ -434,7 +438,9 @@ HatGemmPlan hat_gemm_plan(const HatGemm& g) {
   for (int c = 0; c < kNumTiles; ++c) {
     const TileInfo& q = kTiles[c];
     if (!q.planned) continue;
-    if (large ? q.eff == 0.f : (q.bt & (q.bt - 1)) != 0) continue;   // 160/192/224-row token tiles: large batches only
+    // 160/192/224-row token tiles: large batches only, except the 128 x 160 tile (23), which exists for batches
+    // of 129 .. 160 rows (a second, mostly empty 128-row token tile costs them 15-20 %)
+    if (large ? q.eff == 0.f : ((q.bt & (q.bt - 1)) != 0 && !(c == 23 && g.T > 128 && g.T <= 160))) continue;
     const int nT = (g.T + q.bt - 1) / q.bt, nF = (g.Nw + q.bf - 1) / q.bf;
     const int max_split = (g.epilogue == HAT_EPI_RESID && g.part) ? 16 : 1;
     const int lds = q.nstage * (q.bf + q.bt) * q.bkt * 2;

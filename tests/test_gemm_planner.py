@@ -78,11 +78,16 @@ def test_tile_table_fits_the_hardware(lib):
 
 
 def test_small_batches_keep_power_of_two_token_tiles_and_large_ones_use_the_big_tile(lib):
-    for T in (1, 32, 150, 256, 384):
+    for T in (1, 32, 128, 150, 161, 256, 384):
         for name, (Nw, Nout, K, epi) in SHAPES.items():
             tile, _ = plan(lib, T, Nw, Nout, K, epi, 4096)
             bt = tile_info(lib, tile)[1][1]
-            assert bt & (bt - 1) == 0, "%s at T=%d took a %d-row token tile" % (name, T, bt)
+            # the one exception: 129 .. 160 rows may take the 160-row token tile (one token tile instead of two)
+            assert bt & (bt - 1) == 0 or (bt == 160 and 128 < T <= 160), "%s at T=%d took a %d-row token tile" % (name, T, bt)
+    for name in ("o7", "gu7", "down7", "o13", "gu13", "down13"):     # 30 devices x 5 draft rows: the verify-heavy batch
+        Nw, Nout, K, epi = SHAPES[name]
+        tile, _ = plan(lib, 150, Nw, Nout, K, epi, 4096)
+        assert tile_info(lib, tile)[1][:2] == (128, 160), name
     for name in ("qkv7", "gu7", "qkv13", "gu13"):
         Nw, Nout, K, epi = SHAPES[name]
         tile, ks = plan(lib, 8192, Nw, Nout, K, epi, 4096)
